@@ -1,0 +1,184 @@
+/*
+ * kvp -- block-wise prefill with a fixed-budget KV cache, for AMD MI355X (gfx950).
+ *
+ * The library follows the statement of the method in Alg. 1 of the paper
+ * ("Block-wise Prefill with KV Eviction": input a sequence S, a block size b
+ * and a memory budget M; output the compressed KV cache C).  For every block
+ * and every layer the caller makes two calls:
+ *
+ *   kvp_prefill_chunk   the block's queries attend over cache U block
+ *                       (Eq. 1, Sec. 2.1) and every candidate key receives
+ *                       its importance score (Eq. 4, Sec. 3.2);
+ *   kvp_compact         the block is appended to the cache (Alg. 1 line 7)
+ *                       and, if the cache now exceeds M, the lowest-scored
+ *                       entries are evicted until it holds M (lines 8-11).
+ *
+ * After the last block kvp_decode_ready hands out the cache (Alg. 1 line 13).
+ *
+ * General rules
+ *  - Every function returns KVP_OK (0) or a negative code.  Nothing throws,
+ *    exits, synchronises a stream or allocates device memory: all device
+ *    memory is the single buffer the caller passes to kvp_init_cache.
+ *  - On any error no device work has been enqueued and no state has changed.
+ *  - Pointers named q, k, v, out, scores_override and device_buf are DEVICE
+ *    pointers; cfg, segs and all out-parameters are HOST pointers.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued on it in call order; the caller orders streams.
+ *  - Per layer the calls alternate prefill_chunk, compact, prefill_chunk, ...
+ *    and token ranges are consecutive from 0.  A layer is PENDING between
+ *    its prefill_chunk and its compact, READY otherwise.
+ *  - A kvp_cache is not thread-safe; use one host thread per cache.
+ */
+#ifndef KVP_H
+#define KVP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  KVP_OK = 0,
+  KVP_EINVAL = -1,   /* bad argument, shape, layout or null pointer            */
+  KVP_ESTATE = -2,   /* call out of order for this layer, or tokens skipped    */
+  KVP_ENOMEM = -3,   /* device_buf smaller than kvp_cache_bytes, or host OOM   */
+  KVP_EDEVICE = -4   /* the HIP runtime refused a launch or an event call      */
+};
+
+enum { KVP_TEXT = 0, KVP_VISUAL = 1 };
+
+/* limits */
+enum {
+  KVP_MAX_CANDIDATES = 8192,  /* budget + chunk_max may not exceed this        */
+  KVP_MAX_SEGMENTS = 64
+};
+
+/* One run of consecutive prefix tokens.  Segments must cover [0, N) in order
+ * without gaps.  A visual segment is n_planes planes (tiles of an image or
+ * frames of a video) of grid_h x grid_w patch tokens, row-major inside a
+ * plane, so n_tokens == n_planes * grid_h * grid_w.  Only the merge step reads
+ * the grid; with merge off only token_begin / n_tokens matter. */
+typedef struct kvp_segment {
+  int32_t token_begin;
+  int32_t n_tokens;
+  int32_t kind;       /* KVP_TEXT or KVP_VISUAL */
+  int32_t grid_h;
+  int32_t grid_w;
+  int32_t n_planes;
+  int32_t temporal;   /* 1: adjacent planes are adjacent video frames */
+} kvp_segment;
+
+enum {
+  KVP_FLAG_DRY_RUN = 1  /* validate and advance the host state machine only:
+                           nothing is enqueued, device memory is untouched.
+                           For host-side tests of call order and limits. */
+};
+
+typedef struct kvp_config {
+  int32_t n_layers;
+  int32_t n_q_heads;     /* multiple of n_kv_heads                               */
+  int32_t n_kv_heads;
+  int32_t head_dim;      /* 64 or 128                                            */
+  int32_t budget;        /* M of Alg. 1: slots per KV head per layer, >= 1       */
+  int32_t chunk_max;     /* b of Alg. 1: most tokens per kvp_prefill_chunk       */
+  int32_t merge;         /* 0: eviction only (the paper's method);
+                            1: an evicted visual token is first averaged into its
+                               best kept grid neighbour (this library's addition) */
+  int32_t scratch_sets;  /* how many layers may be PENDING at once (0 means 1);
+                            layer l uses set l % scratch_sets                    */
+  int32_t flags;         /* KVP_FLAG_*                                           */
+  float softmax_scale;   /* 0 means 1/sqrt(head_dim) (Eq. 1)                     */
+} kvp_config;
+
+typedef struct kvp_cache kvp_cache;   /* host object, owned by the library */
+
+const char* kvp_strerror(int code);   /* static string, never NULL */
+
+/* Device bytes kvp_init_cache needs for this configuration (persistent cache
+ * plus scratch), or 0 if the configuration is invalid.  The persistent part is
+ * Eq. 2 at sequence length M plus 8 bytes of metadata per slot. */
+size_t kvp_cache_bytes(const kvp_config* cfg);
+/* The persistent part alone (K, V, token index, weight). */
+size_t kvp_persistent_bytes(const kvp_config* cfg);
+
+/* Create an empty cache (Alg. 1 line 4).  device_buf (256-byte aligned, at
+ * least kvp_cache_bytes(cfg) bytes) stays owned by the caller and must outlive
+ * the cache; the library carves it up.  Enqueues one small fill kernel on
+ * `stream`.  *out receives the host object; release it with kvp_free_cache. */
+int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_segs,
+                   void* device_buf, size_t device_bytes, void* stream, kvp_cache** out);
+
+/* Eq. 1 and Eq. 4 for one block of one layer.
+ *   q   [n_tokens, n_q_heads,  head_dim] bf16, contiguous
+ *   k,v [n_tokens, n_kv_heads, head_dim] bf16, contiguous
+ *   out [n_tokens, n_q_heads,  head_dim] bf16, written
+ * Row r attends to every cached entry and to block keys 0..r.  Scores (the
+ * softmax weights summed over the block's rows and over the query heads that
+ * share a KV head) are left in the layer's scratch set.  k and v must stay
+ * valid, in stream order, until kvp_compact for this layer has been enqueued.
+ * token_begin must be the layer's next unseen token; 1 <= n_tokens <= chunk_max. */
+int kvp_prefill_chunk(kvp_cache* cache, int32_t layer, int32_t token_begin, int32_t n_tokens,
+                      const void* q, const void* k, const void* v, void* out, void* stream);
+
+/* Alg. 1 lines 7-11 for the block last given to kvp_prefill_chunk(layer).
+ * With c cached entries and n block tokens: if c + n <= M all are kept;
+ * otherwise each KV head keeps the M candidates with the highest score, equal
+ * scores by lower token index.  Kept cache rows stay in their slots; kept block
+ * rows, in ascending token order, fill the free slots in ascending order.
+ * scores_override: NULL, or device [n_kv_heads, c + n] fp32 (cache slots
+ * first, then block tokens) used instead of the computed scores. */
+int kvp_compact(kvp_cache* cache, int32_t layer, const float* scores_override, void* stream);
+
+/* The compressed cache of one layer (Alg. 1 line 13).  Device pointers into
+ * device_buf; the first `count` slots of every head are valid; slot order
+ * carries no meaning.  KVP_ESTATE while the layer is PENDING. */
+typedef struct kvp_view {
+  const void* k;              /* [n_kv_heads, budget, head_dim] bf16 */
+  const void* v;              /* [n_kv_heads, budget, head_dim] bf16 */
+  const int32_t* token_idx;   /* [n_kv_heads, budget]                */
+  const float* weight;        /* [n_kv_heads, budget] merge multiplicity, integer-valued */
+  int32_t count;
+  int32_t budget;
+  int32_t next_token;         /* tokens of the prefix seen so far    */
+} kvp_view;
+int kvp_decode_ready(kvp_cache* cache, int32_t layer, kvp_view* out);
+
+/* Resume: declare that the caller has written `count` valid slots per head
+ * into the layer's K, V, token_idx and weight (through the kvp_view pointers)
+ * and that the next block starts at `next_token`.  Layer becomes READY. */
+int kvp_set_state(kvp_cache* cache, int32_t layer, int32_t count, int32_t next_token);
+
+/* Inspection of the last block of a layer (device pointers, valid until the
+ * layer's scratch set is reused).  n_cand = c + n of that block; candidates are
+ * cache slots 0..c-1 then block tokens.
+ *   scores [n_kv_heads, *stride]  fp32, valid after kvp_prefill_chunk
+ *                                 (after kvp_compact they hold the scores used)
+ *   keep   [n_kv_heads, *stride]  uint8, valid after kvp_compact
+ *   dst    [n_kv_heads, *stride]  int32 candidate position merged into, or -1
+ * Any out-pointer may be NULL. */
+int kvp_debug_last(kvp_cache* cache, int32_t layer, const float** scores, const uint8_t** keep,
+                   const int32_t** dst, int32_t* n_cand, int32_t* stride);
+
+/* Per-kernel timing with HIP events on the launching stream.  While enabled
+ * every launch is bracketed by two events.  kvp_profile_read waits for the
+ * recorded events, adds them up per kernel kind and clears them. */
+enum {
+  KVP_K_ATTENTION = 0, KVP_K_COLSUM = 1, KVP_K_SELECT = 2, KVP_K_MERGE = 3,
+  KVP_K_MOVE = 4, KVP_K_COUNT = 5
+};
+typedef struct kvp_kernel_stat {
+  int64_t launches;
+  double total_ms;
+} kvp_kernel_stat;
+int kvp_profile_enable(kvp_cache* cache, int32_t on);
+int kvp_profile_read(kvp_cache* cache, kvp_kernel_stat* stats /* [KVP_K_COUNT] */);
+const char* kvp_kernel_name(int32_t kind);
+
+void kvp_free_cache(kvp_cache* cache);   /* host object only; NULL is fine */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVP_H */

@@ -1,0 +1,463 @@
+// Host side of libkvp: validation, the per-layer state machine of Alg. 1,
+// carving of the caller's device buffer, and kernel sequencing.  No device
+// memory is allocated and no stream is synchronised anywhere in this file
+// except kvp_profile_read, which waits for its own events.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kvp_internal.h"
+
+using namespace kvp;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+  // persistent, per layer strides in bytes
+  size_t k_off, v_off, idx_off, w_off;
+  size_t kv_layer_bytes, meta_layer_elems;
+  size_t persistent_bytes;
+  // global
+  size_t segs_off;
+  // scratch, per set
+  size_t set_off, set_bytes;
+  size_t lse_off, partial_off, scores_off, keep_off, dst_off, counts_off, moves_off, dsts_off,
+      stage_k_off, stage_v_off, stage_w_off;
+  int cand_stride, max_partials, n_sets;
+  size_t total_bytes;
+};
+
+bool valid_config(const kvp_config* c) {
+  if (!c) return false;
+  if (c->n_layers < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return false;
+  if (c->n_q_heads % c->n_kv_heads) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->budget < 1 || c->chunk_max < 1) return false;
+  if ((long long)c->budget + c->chunk_max > KVP_MAX_CANDIDATES) return false;
+  if (c->merge != 0 && c->merge != 1) return false;
+  if (c->scratch_sets < 0 || c->scratch_sets > c->n_layers) return false;
+  if (c->flags & ~KVP_FLAG_DRY_RUN) return false;
+  if (!(c->softmax_scale >= 0.f) || std::isinf(c->softmax_scale)) return false;
+  return true;
+}
+
+Layout make_layout(const kvp_config& c) {
+  Layout L{};
+  const size_t L_ = c.n_layers, H = c.n_kv_heads, M = c.budget, D = c.head_dim, B = c.chunk_max;
+  L.kv_layer_bytes = H * M * D * 2;
+  L.meta_layer_elems = H * M;
+  size_t off = 0;
+  L.k_off = off; off = align_up(off + L_ * L.kv_layer_bytes);
+  L.v_off = off; off = align_up(off + L_ * L.kv_layer_bytes);
+  L.idx_off = off; off = align_up(off + L_ * L.meta_layer_elems * 4);
+  L.w_off = off; off = align_up(off + L_ * L.meta_layer_elems * 4);
+  L.persistent_bytes = off;
+  L.segs_off = off; off = align_up(off + KVP_MAX_SEGMENTS * sizeof(Seg));
+  L.n_sets = c.scratch_sets ? c.scratch_sets : 1;
+  L.cand_stride = (int)((M + B + 63) / 64 * 64);
+  L.max_partials = colsum_max_partials(c.n_q_heads / c.n_kv_heads, c.chunk_max);
+  size_t s = 0;
+  L.lse_off = s; s = align_up(s + (size_t)c.n_q_heads * B * 4);
+  L.partial_off = s; s = align_up(s + H * L.max_partials * L.cand_stride * 4);
+  L.scores_off = s; s = align_up(s + H * L.cand_stride * 4);
+  L.keep_off = s; s = align_up(s + H * L.cand_stride);
+  L.dst_off = s; s = align_up(s + H * L.cand_stride * 4);
+  L.counts_off = s; s = align_up(s + H * sizeof(HeadCounts));
+  L.moves_off = s; s = align_up(s + H * B * sizeof(MoveEntry));
+  L.dsts_off = s; s = align_up(s + H * B * sizeof(DstEntry));
+  L.stage_k_off = s; s = align_up(s + H * B * D * 2);
+  L.stage_v_off = s; s = align_up(s + H * B * D * 2);
+  L.stage_w_off = s; s = align_up(s + H * B * 4);
+  L.set_bytes = s;
+  L.set_off = off;
+  off += L.set_bytes * L.n_sets;
+  L.total_bytes = off;
+  return L;
+}
+
+enum LayerState { READY = 0, PENDING = 1 };
+
+struct Layer {
+  int state = READY;
+  int count = 0;        // entries per head
+  int next_token = 0;
+  // the pending block
+  int t0 = 0, n = 0;
+  const u16* k = nullptr;
+  const u16* v = nullptr;
+  // last block, for kvp_debug_last
+  int last_cand = 0;
+  bool has_last = false;
+};
+
+struct ProfEvent {
+  int kind;
+  hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct kvp_cache {
+  kvp_config cfg;
+  Layout lay;
+  unsigned char* base;
+  int n_tokens;                       // prefix length from the segments
+  std::vector<Seg> segs;
+  std::vector<Layer> layers;
+  std::vector<int> set_owner;         // layer holding each scratch set, or -1
+  float scale;
+  bool dry;
+  bool profiling = false;
+  std::vector<ProfEvent> events;      // recorded, not yet read
+  std::vector<hipEvent_t> pool;       // idle events
+
+  u16* k_cache(int l) const { return reinterpret_cast<u16*>(base + lay.k_off + (size_t)l * lay.kv_layer_bytes); }
+  u16* v_cache(int l) const { return reinterpret_cast<u16*>(base + lay.v_off + (size_t)l * lay.kv_layer_bytes); }
+  int32_t* idx(int l) const { return reinterpret_cast<int32_t*>(base + lay.idx_off) + (size_t)l * lay.meta_layer_elems; }
+  float* weight(int l) const { return reinterpret_cast<float*>(base + lay.w_off) + (size_t)l * lay.meta_layer_elems; }
+  Seg* dev_segs() const { return reinterpret_cast<Seg*>(base + lay.segs_off); }
+  unsigned char* set(int l) const { return base + lay.set_off + (size_t)(l % lay.n_sets) * lay.set_bytes; }
+};
+
+namespace {
+
+// Runs one launch, bracketed by events when profiling.
+template <class F>
+int launch(kvp_cache* c, int kind, hipStream_t s, F&& f) {
+  if (c->dry) return KVP_OK;
+  ProfEvent pe{kind, nullptr, nullptr};
+  if (c->profiling) {
+    for (hipEvent_t* e : {&pe.start, &pe.stop}) {
+      if (!c->pool.empty()) {
+        *e = c->pool.back();
+        c->pool.pop_back();
+      } else if (hipEventCreate(e) != hipSuccess) {
+        return KVP_EDEVICE;
+      }
+    }
+    if (hipEventRecord(pe.start, s) != hipSuccess) return KVP_EDEVICE;
+  }
+  if (f() != hipSuccess) return KVP_EDEVICE;
+  if (c->profiling) {
+    if (hipEventRecord(pe.stop, s) != hipSuccess) return KVP_EDEVICE;
+    c->events.push_back(pe);
+  }
+  return KVP_OK;
+}
+
+int run_compact(kvp_cache* c, int layer, const float* scores_override, hipStream_t s) {
+  Layer& L = c->layers[layer];
+  const kvp_config& cfg = c->cfg;
+  const Layout& lay = c->lay;
+  unsigned char* set = c->set(layer);
+  const int cnt = L.count, n = L.n, M = cfg.budget;
+
+  CompactArgs ca{};
+  ca.k_cache = c->k_cache(layer);
+  ca.v_cache = c->v_cache(layer);
+  ca.token_idx = c->idx(layer);
+  ca.weight = c->weight(layer);
+  ca.k_new = L.k;
+  ca.v_new = L.v;
+  ca.counts = reinterpret_cast<HeadCounts*>(set + lay.counts_off);
+  ca.moves = reinterpret_cast<MoveEntry*>(set + lay.moves_off);
+  ca.dsts = reinterpret_cast<DstEntry*>(set + lay.dsts_off);
+  ca.stage_k = reinterpret_cast<u16*>(set + lay.stage_k_off);
+  ca.stage_v = reinterpret_cast<u16*>(set + lay.stage_v_off);
+  ca.stage_w = reinterpret_cast<float*>(set + lay.stage_w_off);
+  ca.c = cnt; ca.n = n; ca.t0 = L.t0; ca.budget = M;
+  ca.n_kv_heads = cfg.n_kv_heads; ca.head_dim = cfg.head_dim; ca.chunk_max = cfg.chunk_max;
+  const int rpb = rows_per_compact_block();
+
+  if (cnt + n <= M) {
+    // Alg. 1 line 8 is false: plain append
+    ca.identity = 1;
+    ca.blocks_per_head = (n + rpb - 1) / rpb;
+    int rc = launch(c, KVP_K_MOVE, s, [&] { return launch_move(ca, s); });
+    if (rc) return rc;
+    L.count = cnt + n;
+    return KVP_OK;
+  }
+
+  SelectArgs sa{};
+  sa.partial = scores_override ? nullptr : reinterpret_cast<const float*>(set + lay.partial_off);
+  sa.score_override = scores_override;
+  sa.scores = reinterpret_cast<float*>(set + lay.scores_off);
+  sa.keep = set + lay.keep_off;
+  sa.dst = reinterpret_cast<int32_t*>(set + lay.dst_off);
+  sa.token_idx = c->idx(layer);
+  sa.counts = reinterpret_cast<HeadCounts*>(set + lay.counts_off);
+  sa.moves = reinterpret_cast<MoveEntry*>(set + lay.moves_off);
+  sa.dsts = reinterpret_cast<DstEntry*>(set + lay.dsts_off);
+  sa.segs = c->dev_segs();
+  sa.n_segs = (int)c->segs.size();
+  sa.c = cnt; sa.n = n; sa.t0 = L.t0; sa.budget = M;
+  sa.cand_stride = lay.cand_stride; sa.chunk_max = cfg.chunk_max;
+  {
+    // the partial count of the attention pass that produced the scores
+    ColsumArgs tmp{};
+    tmp.n = n; tmp.c = cnt; tmp.n_q_heads = cfg.n_q_heads; tmp.n_kv_heads = cfg.n_kv_heads;
+    plan_colsum(tmp, cfg.head_dim);
+    sa.n_partials = tmp.n_partials;
+  }
+  sa.merge = cfg.merge;
+  sa.items = (cnt + n + 1023) / 1024;
+  int ts = 2;
+  while (ts < 2 * (cnt + n)) ts <<= 1;
+  sa.table_size = ts;
+  int rc = launch(c, KVP_K_SELECT, s, [&] { return launch_select(sa, cfg.n_kv_heads, s); });
+  if (rc) return rc;
+
+  ca.identity = 0;
+  const int n_evict = cnt + n - M;
+  if (cfg.merge) {
+    const int max_dst = n_evict < cfg.chunk_max ? n_evict : cfg.chunk_max;
+    ca.blocks_per_head = (max_dst + rpb - 1) / rpb;
+    rc = launch(c, KVP_K_MERGE, s, [&] { return launch_merge(ca, s); });
+    if (rc) return rc;
+  }
+  ca.blocks_per_head = (n + rpb - 1) / rpb;
+  rc = launch(c, KVP_K_MOVE, s, [&] { return launch_move(ca, s); });
+  if (rc) return rc;
+  L.count = M;
+  return KVP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* kvp_strerror(int code) {
+  switch (code) {
+    case KVP_OK: return "ok";
+    case KVP_EINVAL: return "invalid argument";
+    case KVP_ESTATE: return "call out of order for this layer";
+    case KVP_ENOMEM: return "buffer too small or out of host memory";
+    case KVP_EDEVICE: return "HIP runtime error";
+    default: return "unknown kvp error";
+  }
+}
+
+const char* kvp_kernel_name(int32_t kind) {
+  switch (kind) {
+    case KVP_K_ATTENTION: return "attention";
+    case KVP_K_COLSUM: return "colsum";
+    case KVP_K_SELECT: return "select";
+    case KVP_K_MERGE: return "merge";
+    case KVP_K_MOVE: return "move";
+    default: return "?";
+  }
+}
+
+size_t kvp_cache_bytes(const kvp_config* cfg) {
+  if (!valid_config(cfg)) return 0;
+  return make_layout(*cfg).total_bytes;
+}
+
+size_t kvp_persistent_bytes(const kvp_config* cfg) {
+  if (!valid_config(cfg)) return 0;
+  return make_layout(*cfg).persistent_bytes;
+}
+
+int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_segs, void* device_buf,
+                   size_t device_bytes, void* stream, kvp_cache** out) {
+  if (!out) return KVP_EINVAL;
+  *out = nullptr;
+  if (!valid_config(cfg) || !segs || n_segs < 1 || n_segs > KVP_MAX_SEGMENTS) return KVP_EINVAL;
+  const bool dry = cfg->flags & KVP_FLAG_DRY_RUN;
+  if (!dry && (!device_buf || (reinterpret_cast<uintptr_t>(device_buf) % kAlign))) return KVP_EINVAL;
+  long long t = 0;
+  for (int i = 0; i < n_segs; ++i) {
+    const kvp_segment& s = segs[i];
+    if (s.token_begin != t || s.n_tokens < 1) return KVP_EINVAL;
+    if (s.kind == KVP_VISUAL) {
+      if (s.grid_h < 1 || s.grid_w < 1 || s.n_planes < 1) return KVP_EINVAL;
+      if ((long long)s.grid_h * s.grid_w * s.n_planes != s.n_tokens) return KVP_EINVAL;
+      if (s.temporal != 0 && s.temporal != 1) return KVP_EINVAL;
+    } else if (s.kind != KVP_TEXT) {
+      return KVP_EINVAL;
+    }
+    t += s.n_tokens;
+    if (t > 0x7FFFFFFF) return KVP_EINVAL;
+  }
+  const Layout lay = make_layout(*cfg);
+  if (!dry && device_bytes < lay.total_bytes) return KVP_ENOMEM;
+
+  kvp_cache* c = new (std::nothrow) kvp_cache();
+  if (!c) return KVP_ENOMEM;
+  c->cfg = *cfg;
+  c->lay = lay;
+  c->base = static_cast<unsigned char*>(device_buf);
+  c->n_tokens = (int)t;
+  c->dry = dry;
+  c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.f / std::sqrt((float)cfg->head_dim);
+  for (int i = 0; i < n_segs; ++i)
+    c->segs.push_back(Seg{segs[i].token_begin, segs[i].n_tokens, segs[i].kind, segs[i].grid_h,
+                          segs[i].grid_w, segs[i].n_planes, segs[i].temporal});
+  c->layers.resize(cfg->n_layers);
+  c->set_owner.assign(lay.n_sets, -1);
+  if (!dry) {
+    const size_t slots = (size_t)cfg->n_layers * lay.meta_layer_elems;
+    hipError_t e = launch_init(c->idx(0), c->weight(0), slots, c->segs.data(), n_segs, c->dev_segs(),
+                               static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+      delete c;
+      return KVP_EDEVICE;
+    }
+  }
+  *out = c;
+  return KVP_OK;
+}
+
+int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
+                      const void* k, const void* v, void* out, void* stream) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  if (n_tokens < 1 || n_tokens > c->cfg.chunk_max) return KVP_EINVAL;
+  if (!c->dry && (!q || !k || !v || !out)) return KVP_EINVAL;
+  Layer& L = c->layers[layer];
+  if (L.state != READY) return KVP_ESTATE;
+  if (token_begin != L.next_token) return KVP_ESTATE;
+  if ((long long)token_begin + n_tokens > c->n_tokens) return KVP_EINVAL;
+  const int set_i = layer % c->lay.n_sets;
+  if (c->set_owner[set_i] != -1) return KVP_ESTATE;   // another layer's block is still pending there
+
+  const kvp_config& cfg = c->cfg;
+  const Layout& lay = c->lay;
+  unsigned char* set = c->set(layer);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  AttnArgs aa{};
+  aa.q = static_cast<const u16*>(q);
+  aa.k_new = static_cast<const u16*>(k);
+  aa.v_new = static_cast<const u16*>(v);
+  aa.out = static_cast<u16*>(out);
+  aa.k_cache = c->k_cache(layer);
+  aa.v_cache = c->v_cache(layer);
+  aa.lse2 = reinterpret_cast<float*>(set + lay.lse_off);
+  aa.n = n_tokens; aa.c = L.count;
+  aa.n_q_heads = cfg.n_q_heads; aa.n_kv_heads = cfg.n_kv_heads;
+  aa.budget = cfg.budget; aa.lse_stride = cfg.chunk_max;
+  aa.scale_log2 = c->scale * 1.4426950408889634f;
+  plan_attention(aa, cfg.head_dim);
+  int rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
+  if (rc) return rc;
+
+  ColsumArgs cs{};
+  cs.q = aa.q; cs.k_new = aa.k_new; cs.k_cache = aa.k_cache; cs.lse2 = aa.lse2;
+  cs.partial = reinterpret_cast<float*>(set + lay.partial_off);
+  cs.n = n_tokens; cs.c = L.count;
+  cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
+  cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
+  cs.scale_log2 = aa.scale_log2;
+  plan_colsum(cs, cfg.head_dim);
+  rc = launch(c, KVP_K_COLSUM, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
+  if (rc) return rc;
+
+  L.state = PENDING;
+  L.t0 = token_begin; L.n = n_tokens;
+  L.k = aa.k_new; L.v = aa.v_new;
+  L.last_cand = L.count + n_tokens;
+  L.has_last = true;
+  c->set_owner[set_i] = layer;
+  return KVP_OK;
+}
+
+int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void* stream) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  Layer& L = c->layers[layer];
+  if (L.state != PENDING) return KVP_ESTATE;
+  const int before = L.count;
+  int rc = run_compact(c, layer, scores_override, static_cast<hipStream_t>(stream));
+  if (rc) {
+    L.count = before;
+    return rc;
+  }
+  L.state = READY;
+  L.next_token = L.t0 + L.n;
+  c->set_owner[layer % c->lay.n_sets] = -1;
+  return KVP_OK;
+}
+
+int kvp_decode_ready(kvp_cache* c, int32_t layer, kvp_view* out) {
+  if (!c || !out || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  const Layer& L = c->layers[layer];
+  if (L.state != READY) return KVP_ESTATE;
+  out->k = c->k_cache(layer);
+  out->v = c->v_cache(layer);
+  out->token_idx = c->idx(layer);
+  out->weight = c->weight(layer);
+  out->count = L.count;
+  out->budget = c->cfg.budget;
+  out->next_token = L.next_token;
+  return KVP_OK;
+}
+
+int kvp_set_state(kvp_cache* c, int32_t layer, int32_t count, int32_t next_token) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  if (count < 0 || count > c->cfg.budget) return KVP_EINVAL;
+  if (next_token < 0 || next_token > c->n_tokens || count > next_token) return KVP_EINVAL;
+  Layer& L = c->layers[layer];
+  const int set_i = layer % c->lay.n_sets;
+  if (L.state == PENDING && c->set_owner[set_i] == layer) c->set_owner[set_i] = -1;
+  L.state = READY;
+  L.count = count;
+  L.next_token = next_token;
+  L.has_last = false;
+  return KVP_OK;
+}
+
+int kvp_debug_last(kvp_cache* c, int32_t layer, const float** scores, const uint8_t** keep,
+                   const int32_t** dst, int32_t* n_cand, int32_t* stride) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  const Layer& L = c->layers[layer];
+  if (!L.has_last) return KVP_ESTATE;
+  unsigned char* set = c->set(layer);
+  if (scores) *scores = reinterpret_cast<const float*>(set + c->lay.scores_off);
+  if (keep) *keep = set + c->lay.keep_off;
+  if (dst) *dst = reinterpret_cast<const int32_t*>(set + c->lay.dst_off);
+  if (n_cand) *n_cand = L.last_cand;
+  if (stride) *stride = c->lay.cand_stride;
+  return KVP_OK;
+}
+
+int kvp_profile_enable(kvp_cache* c, int32_t on) {
+  if (!c) return KVP_EINVAL;
+  c->profiling = on != 0 && !c->dry;
+  return KVP_OK;
+}
+
+int kvp_profile_read(kvp_cache* c, kvp_kernel_stat* stats) {
+  if (!c || !stats) return KVP_EINVAL;
+  for (int i = 0; i < KVP_K_COUNT; ++i) stats[i] = kvp_kernel_stat{0, 0.0};
+  int rc = KVP_OK;
+  for (ProfEvent& pe : c->events) {
+    float ms = 0.f;
+    if (hipEventSynchronize(pe.stop) != hipSuccess || hipEventElapsedTime(&ms, pe.start, pe.stop) != hipSuccess) {
+      rc = KVP_EDEVICE;
+    } else {
+      stats[pe.kind].launches += 1;
+      stats[pe.kind].total_ms += ms;
+    }
+    c->pool.push_back(pe.start);
+    c->pool.push_back(pe.stop);
+  }
+  c->events.clear();
+  return rc;
+}
+
+void kvp_free_cache(kvp_cache* c) {
+  if (!c) return;
+  for (ProfEvent& pe : c->events) {
+    hipEventDestroy(pe.start);
+    hipEventDestroy(pe.stop);
+  }
+  for (hipEvent_t e : c->pool) hipEventDestroy(e);
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,119 @@
+// Internal declarations shared by the host state machine and the kernel
+// launchers of libkvp.  Not part of the public interface.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvp.h"
+
+namespace kvp {
+
+typedef unsigned short u16;  // one bfloat16 bit pattern
+
+constexpr int kXcds = 8;            // MI355X: 8 accelerator dies, each with its own L2
+constexpr int kNeighbours = 6;      // 4 in the plane + 2 in time
+
+// One block of one layer attending over cache U block (Eq. 1).
+struct AttnArgs {
+  const u16* q;        // [n, Hq, D]
+  const u16* k_new;    // [n, Hkv, D]
+  const u16* v_new;    // [n, Hkv, D]
+  u16* out;            // [n, Hq, D]
+  const u16* k_cache;  // this layer: [Hkv, M, D]
+  const u16* v_cache;
+  float* lse2;         // [Hq, lse_stride]  log2-domain log-sum-exp of every row
+  int n, c, n_q_heads, n_kv_heads, budget, lse_stride;
+  int n_row_tiles, work_per_xcd, total_work;
+  int variant;         // tile shape, chosen by plan_attention
+  float scale_log2;    // softmax scale times log2(e)
+};
+
+// Column sums of the softmax matrix (Eq. 4 summed over rows), one partial
+// array per (query head of the group, row split).
+struct ColsumArgs {
+  const u16* q;
+  const u16* k_new;
+  const u16* k_cache;
+  const float* lse2;
+  float* partial;      // [Hkv, n_partials, cand_stride]
+  int n, c, n_q_heads, n_kv_heads, budget, lse_stride, cand_stride;
+  int n_kv_blocks, row_splits, q_tiles_per_split, n_partials;
+  int work_per_xcd, total_work;
+  float scale_log2;
+};
+
+// Device copy of one prefix segment.
+struct Seg {
+  int begin, n, kind, gh, gw, planes, temporal;
+};
+
+// Per-head outputs of the select kernel, inputs of merge and move.
+struct HeadCounts {
+  int n_moves;   // kept block tokens = free slots filled
+  int n_dst;     // merge destinations that have at least one source
+  int pad0, pad1;
+};
+struct MoveEntry {
+  int pos;    // candidate position (>= c) of the kept block token
+  int slot;   // cache slot it goes to
+  int stage;  // index into the staging rows if the token is a merge destination, else -1
+  int pad;
+};
+struct DstEntry {
+  int pos;                  // candidate position of the destination
+  int n_src;
+  int src[kNeighbours];     // candidate positions of its sources
+};
+
+struct SelectArgs {
+  const float* partial;         // [Hkv, n_partials, cand_stride] or null when override is set
+  const float* score_override;  // [Hkv, n_cand] or null
+  float* scores;                // [Hkv, cand_stride]   scores actually used
+  uint8_t* keep;                // [Hkv, cand_stride]
+  int32_t* dst;                 // [Hkv, cand_stride]
+  const int32_t* token_idx;     // this layer: [Hkv, M]
+  HeadCounts* counts;           // [Hkv]
+  MoveEntry* moves;             // [Hkv, chunk_max]
+  DstEntry* dsts;               // [Hkv, chunk_max]
+  const Seg* segs;
+  int n_segs;
+  int c, n, t0, budget, cand_stride, chunk_max, n_partials, merge;
+  int items;                    // candidates per thread
+  int table_size;               // power of two >= 2 * (c + n)
+};
+
+struct CompactArgs {
+  u16* k_cache;            // this layer
+  u16* v_cache;
+  int32_t* token_idx;
+  float* weight;
+  const u16* k_new;
+  const u16* v_new;
+  const HeadCounts* counts;
+  const MoveEntry* moves;
+  const DstEntry* dsts;
+  u16* stage_k;            // [Hkv, chunk_max, D]
+  u16* stage_v;
+  float* stage_w;          // [Hkv, chunk_max]
+  int c, n, t0, budget, n_kv_heads, head_dim, chunk_max;
+  int identity;            // 1: plain append of all n tokens to slots c..c+n-1
+  int blocks_per_head;
+};
+
+// launchers (each returns the hipError_t of the launch)
+hipError_t launch_attention(const AttnArgs& a, int head_dim, hipStream_t s);
+hipError_t launch_colsum(const ColsumArgs& a, int head_dim, hipStream_t s);
+hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s);
+hipError_t launch_merge(const CompactArgs& a, hipStream_t s);
+hipError_t launch_move(const CompactArgs& a, hipStream_t s);
+hipError_t launch_init(int32_t* token_idx, float* weight, size_t n_slots, const Seg* host_segs,
+                       int n_segs, Seg* dev_segs, hipStream_t s);
+int rows_per_compact_block();
+
+// host-side planning shared by launchers and the state machine
+void plan_attention(AttnArgs& a, int head_dim);
+void plan_colsum(ColsumArgs& a, int head_dim);
+int colsum_max_partials(int group, int chunk_max);
+size_t select_lds_bytes(int n_cand, int items, int table_size);
+
+}  // namespace kvp

@@ -1,0 +1,166 @@
+"""Host-side checks that need no GPU: the library loads, exports every declared
+symbol, sizes follow Eq. 2, and the per-layer state machine of Alg. 1 rejects
+bad calls without touching the device (dry-run caches enqueue nothing)."""
+import ctypes
+
+import pytest
+
+import paper_2604_16734_amd as K
+from kvp_workload import WORKLOADS, get_workload, chunk_ranges
+from oracle import kvp_oracle as O
+
+
+def _cfg(wl, merge=1, sets=1, flags=K.KVP_FLAG_DRY_RUN, **over):
+    c = K.KvpConfig(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
+                    merge, sets, flags, 0.0)
+    for k, v in over.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_library_exports_every_declared_symbol():
+    L = K.lib()
+    names = K.declared_symbols()
+    assert {"kvp_init_cache", "kvp_prefill_chunk", "kvp_compact", "kvp_decode_ready"} <= set(names)
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_strerror_and_kernel_names():
+    assert K.kvp_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert K.kvp_strerror(code)
+    assert [K.kvp_kernel_name(i) for i in range(5)] == list(K.KERNEL_KINDS)
+
+
+def test_persistent_bytes_follow_eq2():
+    # Eq. 2 at sequence length M, bf16, plus 8 bytes of metadata per slot
+    for wl in WORKLOADS:
+        cfg = _cfg(wl)
+        kv = O.kv_cache_bytes(wl.n_layers, wl.n_kv_heads, wl.head_dim, 2, wl.budget)
+        meta = 8 * wl.n_layers * wl.n_kv_heads * wl.budget
+        assert K.kvp_persistent_bytes(cfg) == kv + meta
+        total = K.kvp_cache_bytes(cfg)
+        assert total > kv + meta
+        # two scratch sets cost exactly one more set
+        total2 = K.kvp_cache_bytes(_cfg(wl, sets=2 if wl.n_layers > 1 else 1))
+        assert total2 >= total
+
+
+@pytest.mark.parametrize("field,value", [
+    ("n_layers", 0), ("n_q_heads", 5), ("n_kv_heads", 0), ("head_dim", 96), ("budget", 0),
+    ("chunk_max", 0), ("merge", 2), ("scratch_sets", -1), ("flags", 8), ("softmax_scale", -1.0),
+    ("budget", 8190),
+])
+def test_invalid_config_rejected(field, value):
+    wl = get_workload("tiny")
+    cfg = _cfg(wl, **{field: value})
+    assert K.kvp_cache_bytes(cfg) == 0
+    rc, h = K.kvp_init_cache(cfg, wl.segments, None, 0)
+    assert rc == K.KVP_EINVAL and not h
+
+
+def test_segment_validation():
+    wl = get_workload("tiny")
+    cfg = _cfg(wl)
+    S = K.KvpSegment
+    bad = [
+        [S(0, 10, 1, 2, 5, 1, 0), S(11, 5, 0, 0, 0, 0, 0)],      # gap
+        [S(1, 10, 0, 0, 0, 0, 0)],                               # does not start at 0
+        [S(0, 10, 1, 3, 3, 1, 0)],                               # 3*3*1 != 10
+        [S(0, 10, 2, 0, 0, 0, 0)],                               # unknown kind
+        [S(0, 0, 0, 0, 0, 0, 0)],                                # empty
+        [S(0, 8, 1, 2, 2, 2, 5)],                                # temporal flag
+    ]
+    for segs in bad:
+        rc, h = K.kvp_init_cache(cfg, segs, None, 0)
+        assert rc == K.KVP_EINVAL and not h
+    rc, h = K.kvp_init_cache(cfg, [], None, 0)
+    assert rc == K.KVP_EINVAL
+
+
+def test_device_buffer_checks_without_dry_run():
+    wl = get_workload("tiny")
+    cfg = _cfg(wl, flags=0)
+    need = K.kvp_cache_bytes(cfg)
+    rc, h = K.kvp_init_cache(cfg, wl.segments, None, need)            # null buffer
+    assert rc == K.KVP_EINVAL and not h
+    rc, h = K.kvp_init_cache(cfg, wl.segments, 4096 + 8, need)        # misaligned
+    assert rc == K.KVP_EINVAL and not h
+    rc, h = K.kvp_init_cache(cfg, wl.segments, 4096, need - 1)        # too small
+    assert rc == K.KVP_ENOMEM and not h
+
+
+def test_state_machine_and_counts():
+    wl = get_workload("tiled_image")
+    cfg = _cfg(wl)
+    rc, h = K.kvp_init_cache(cfg, wl.segments, None, 0)
+    assert rc == K.KVP_OK and h
+    try:
+        # compact before any block, and decode view of an empty layer
+        assert K.kvp_compact(h, 0) == K.KVP_ESTATE
+        rc, vw = K.kvp_decode_ready(h, 0)
+        assert rc == K.KVP_OK and vw.count == 0 and vw.budget == wl.budget and vw.next_token == 0
+        # bad layer / sizes / order
+        assert K.kvp_prefill_chunk(h, wl.n_layers, 0, 8, 0, 0, 0, 0) == K.KVP_EINVAL
+        assert K.kvp_prefill_chunk(h, -1, 0, 8, 0, 0, 0, 0) == K.KVP_EINVAL
+        assert K.kvp_prefill_chunk(h, 0, 0, 0, 0, 0, 0, 0) == K.KVP_EINVAL
+        assert K.kvp_prefill_chunk(h, 0, 0, wl.chunk + 1, 0, 0, 0, 0) == K.KVP_EINVAL
+        assert K.kvp_prefill_chunk(h, 0, 5, 8, 0, 0, 0, 0) == K.KVP_ESTATE          # tokens skipped
+        # the whole prefix, counts follow min(M, c + n) (Alg. 1 lines 8-11)
+        count = 0
+        for t0, n in chunk_ranges(wl.n_tokens, wl.chunk):
+            for layer in range(wl.n_layers):
+                assert K.kvp_prefill_chunk(h, layer, t0, n, 0, 0, 0, 0) == K.KVP_OK
+                assert K.kvp_prefill_chunk(h, layer, t0 + n, 1, 0, 0, 0, 0) == K.KVP_ESTATE   # pending
+                rc, _ = K.kvp_decode_ready(h, layer)
+                assert rc == K.KVP_ESTATE
+                assert K.kvp_compact(h, layer) == K.KVP_OK
+                assert K.kvp_compact(h, layer) == K.KVP_ESTATE
+                rc, vw = K.kvp_decode_ready(h, layer)
+                assert rc == K.KVP_OK and vw.count == min(wl.budget, count + n) and vw.next_token == t0 + n
+            count = min(wl.budget, count + n)
+        # past the end of the prefix
+        assert K.kvp_prefill_chunk(h, 0, wl.n_tokens, 1, 0, 0, 0, 0) == K.KVP_EINVAL
+        # restore
+        assert K.kvp_set_state(h, 0, wl.budget + 1, 10) == K.KVP_EINVAL
+        assert K.kvp_set_state(h, 0, 10, 5) == K.KVP_EINVAL
+        assert K.kvp_set_state(h, 0, 100, 300) == K.KVP_OK
+        rc, vw = K.kvp_decode_ready(h, 0)
+        assert vw.count == 100 and vw.next_token == 300
+        assert K.kvp_prefill_chunk(h, 0, 300, 16, 0, 0, 0, 0) == K.KVP_OK
+    finally:
+        K.kvp_free_cache(h)
+
+
+def test_scratch_sets_gate_pending_layers():
+    wl = get_workload("single_image")
+    for sets, second_ok in ((1, False), (2, True)):
+        rc, h = K.kvp_init_cache(_cfg(wl, sets=sets), wl.segments, None, 0)
+        assert rc == K.KVP_OK
+        try:
+            assert K.kvp_prefill_chunk(h, 0, 0, 16, 0, 0, 0, 0) == K.KVP_OK
+            rc = K.kvp_prefill_chunk(h, 1, 0, 16, 0, 0, 0, 0)
+            assert rc == (K.KVP_OK if second_ok else K.KVP_ESTATE)
+            # layer 2 shares set 0 with layer 0 when there are two sets
+            assert K.kvp_prefill_chunk(h, 2, 0, 16, 0, 0, 0, 0) == K.KVP_ESTATE
+            assert K.kvp_compact(h, 0) == K.KVP_OK
+            assert K.kvp_prefill_chunk(h, 2, 0, 16, 0, 0, 0, 0) == K.KVP_OK
+        finally:
+            K.kvp_free_cache(h)
+
+
+def test_null_handles():
+    assert K.kvp_compact(None, 0) == K.KVP_EINVAL
+    assert K.kvp_prefill_chunk(None, 0, 0, 1, 0, 0, 0, 0) == K.KVP_EINVAL
+    rc, _ = K.kvp_decode_ready(None, 0)
+    assert rc == K.KVP_EINVAL
+    K.kvp_free_cache(None)
+    wl = get_workload("tiny")
+    rc, h = K.kvp_init_cache(_cfg(wl, flags=0), wl.segments, 4096, 1 << 30)
+    # a real (non dry-run) cache refuses null tensors before launching anything
+    if rc == K.KVP_OK:
+        assert K.kvp_prefill_chunk(h, 0, 0, 8, 0, 0, 0, 0) == K.KVP_EINVAL
+        K.kvp_free_cache(h)
+    else:
+        assert rc == K.KVP_EDEVICE      # no GPU here: the init kernel could not be enqueued
