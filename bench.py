@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the compress-as-you-prefill hot path on one MI355X.
+
+A "step" is one whole prefill of the workload: every block of the prefix
+through every layer, each as kvp_prefill_chunk (attention + scoring) followed
+by kvp_compact (select + merge + move), with Q, K, V of all layers already
+resident in HBM.  The metric is prefill tokens/s at the fixed KV budget.
+
+Prints ONE JSON line.  `roofline` is for the attention kernel (the dominant
+one): algorithmic flops 4 d Hq (n c + n (n + 1) / 2) per launch over its HIP
+event time on the launching stream.  `cpu_baseline` is the NumPy oracle timed
+on this machine's host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, vendor figure
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, vendor figure
+# HBM bytes per attention launch (fetch + write) at the long_video steady state, from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/; None until measured
+ATTENTION_TRAFFIC_BYTES = {}
+
+
+def attention_flops(wl, t0_n_pairs):
+    """Algorithmic flops of the attention launches of one layer over the given blocks."""
+    total = 0
+    c = 0
+    per = []
+    for _, n in t0_n_pairs:
+        f = 4 * wl.head_dim * wl.n_q_heads * (n * c + n * (n + 1) // 2)
+        per.append(f)
+        total += f
+        c = min(wl.budget, c + n)
+    return total, per
+
+
+def generate(wl, device, threads):
+    import torch
+    from kvp_workload import layer_inputs
+    from tests.gpu_util import bits_to_torch
+
+    def one(layer):
+        return layer_inputs(wl, layer)
+
+    out = []
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for qb, kb, vb in ex.map(one, range(wl.n_layers)):
+            out.append(tuple(bits_to_torch(x, device) for x in (qb, kb, vb)))
+    torch.cuda.synchronize()
+    return out
+
+
+def run_steps(cache, wl, data, ranges, steps, outs):
+    for _ in range(steps):
+        for layer in range(wl.n_layers):
+            cache.set_state(layer, 0, 0)
+        for t0, n in ranges:
+            for layer in range(wl.n_layers):
+                q, k, v = data[layer]
+                cache.prefill_chunk(layer, t0, q[t0:t0 + n], k[t0:t0 + n], v[t0:t0 + n], out=outs[layer][:n])
+                cache.compact(layer)
+
+
+def bench_workload(wl, steps, warmup, device, threads, profile=True):
+    import torch
+    import paper_2604_16734_amd as K
+    from kvp_workload import chunk_ranges
+
+    data = generate(wl, device, threads)
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    cache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
+                    wl.segments, merge=True, scratch_sets=1, device=device)
+    outs = [torch.empty((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=device)
+            for _ in range(wl.n_layers)]
+    run_steps(cache, wl, data, ranges, warmup, outs)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    run_steps(cache, wl, data, ranges, steps, outs)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+    ms_per_step = 1e3 * elapsed / steps
+    res = {
+        "tokens_per_s": wl.n_tokens / (elapsed / steps),
+        "ms_per_step": ms_per_step,
+        "persistent_kv_bytes": cache.persistent_bytes,
+        "scratch_bytes": cache.nbytes - cache.persistent_bytes,
+        "chunk_kv_bytes": 2 * wl.chunk * wl.n_kv_heads * wl.head_dim * 2,
+        "full_cache_kv_bytes": 2 * wl.n_layers * wl.n_kv_heads * wl.head_dim * 2 * wl.n_tokens,
+    }
+    if profile:
+        prof_steps = 1
+        cache.profile_enable(True)
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        run_steps(cache, wl, data, ranges, prof_steps, outs)
+        torch.cuda.synchronize()
+        res["profiled_ms_per_step"] = 1e3 * (time.perf_counter() - t_begin) / prof_steps
+        stats = cache.profile_read()
+        cache.profile_enable(False)
+        flops_layer, _ = attention_flops(wl, ranges)
+        flops_step = flops_layer * wl.n_layers
+        kern = {}
+        for name, (launches, ms) in stats.items():
+            if launches:
+                kern[name] = {"launches_per_step": launches // prof_steps, "ms_per_step": ms / prof_steps,
+                              "avg_us": 1e3 * ms / launches}
+        res["kernels"] = kern
+        att_ms = stats["attention"][1] / prof_steps
+        col_ms = stats["colsum"][1] / prof_steps
+        res["attention_tflops"] = flops_step / (att_ms * 1e-3) / 1e12
+        res["attention_plus_scoring_tflops"] = flops_step / ((att_ms + col_ms) * 1e-3) / 1e12
+        res["attention_flops_per_launch"] = flops_step / stats["attention"][0] * prof_steps
+        # bytes the compaction kernels must move: per kept block row 2 x (read + write) of d bf16
+        row = wl.head_dim * 2
+        moved = 0
+        c = 0
+        for _, n in ranges:
+            moved += 2 * 2 * row * n * wl.n_kv_heads        # every block row is written once at most
+            c = min(wl.budget, c + n)
+        res["move_bytes_bound_per_step"] = moved * wl.n_layers
+    cache.close()
+    del data
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(wl, budget_s=15.0):
+    """The oracle as it stands on this machine's host cores, one layer, as many blocks as fit
+    in the time budget; scaled to whole-job tokens/s by the layer count."""
+    import numpy as np
+    from kvp_workload import layer_inputs, bf16_bits_to_f32, chunk_ranges
+    from oracle import kvp_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    qb, kb, vb = layer_inputs(wl, 0)
+    q, k, v = (bf16_bits_to_f32(x).astype(np.float64) for x in (qb, kb, vb))
+    oc = O.LayerCache(wl.n_kv_heads, wl.head_dim, wl.budget, wl.segments, True)
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    done_tokens, done_blocks = 0, 0
+    t_begin = time.perf_counter()
+    for t0, n in ranges:
+        oc.step(t0, q[t0:t0 + n], k[t0:t0 + n], v[t0:t0 + n])
+        done_tokens += n
+        done_blocks += 1
+        if time.perf_counter() - t_begin > budget_s:
+            break
+    elapsed = time.perf_counter() - t_begin
+    return {
+        "value": done_tokens / (elapsed * wl.n_layers),
+        "unit": "tokens/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": "layer 0 of %d, first %d of %d blocks (%d tokens) in %.1f s, float64 NumPy; "
+                  "scaled by the layer count" % (wl.n_layers, done_blocks, len(ranges), done_tokens, elapsed),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="long_video")
+    ap.add_argument("--others", type=int, default=1, help="also time the other four shapes (few steps)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (no collectives, "
+              "nothing to shard: see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_16734_amd as K
+    from kvp_workload import WORKLOADS, get_workload
+    K.lib()                                   # fail loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    device = "cuda:0"
+    threads = min(16, len(os.sched_getaffinity(0)))
+    wl = get_workload(args.workload)
+    main_res = bench_workload(wl, args.steps, args.warmup, device, threads)
+
+    others = {}
+    if args.others:
+        for w in WORKLOADS:
+            if w.name != wl.name:
+                r = bench_workload(w, max(3, args.steps // 2), 2, device, threads, profile=True)
+                others[w.name] = {
+                    "tokens_per_s": round(r["tokens_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4),
+                    "attention_tflops": round(r["attention_tflops"], 2),
+                    "attention_plus_scoring_tflops": round(r["attention_plus_scoring_tflops"], 2),
+                    "persistent_kv_bytes": r["persistent_kv_bytes"],
+                }
+
+    att = main_res["kernels"]["attention"]
+    achieved = main_res["attention_tflops"]
+    line = {
+        "metric": "prefill tokens/s at fixed KV budget (1 GPU)",
+        "value": round(main_res["tokens_per_s"], 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name, "n_layers": wl.n_layers, "n_q_heads": wl.n_q_heads,
+            "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "prefix_tokens": wl.n_tokens,
+            "chunk": wl.chunk, "kv_budget_per_head": wl.budget, "merge": 1,
+            "step": "whole prefill: all blocks x all layers of prefill_chunk + compact",
+        },
+        "roofline": {
+            "kernel": "attention",
+            "bound": "mfma",
+            "achieved": round(achieved, 2),
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+            "traffic": ATTENTION_TRAFFIC_BYTES.get(wl.name),
+            "avg_launch_us": round(att["avg_us"], 2),
+            "flops_per_launch": main_res["attention_flops_per_launch"],
+            "attention_plus_scoring_tflops": round(main_res["attention_plus_scoring_tflops"], 2),
+            "attention_plus_scoring_frac": round(main_res["attention_plus_scoring_tflops"] / PEAK_BF16_TFLOPS, 4),
+        },
+        "kernels": {k: {kk: round(vv, 3) for kk, vv in v.items()} for k, v in main_res["kernels"].items()},
+        "profiled_ms_per_step": round(main_res["profiled_ms_per_step"], 4),
+        "peak_kv_bytes": {
+            "persistent": main_res["persistent_kv_bytes"],
+            "scratch": main_res["scratch_bytes"],
+            "one_block_kv_in_flight": main_res["chunk_kv_bytes"],
+            "full_cache_would_be": main_res["full_cache_kv_bytes"],
+        },
+        "other_workloads": others,
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
