@@ -6,18 +6,25 @@
 // held in registers for the whole kernel) and O^T = V^T P^T (A operand = V^T
 // from LDS, B operand = P^T).  In the 32x32 accumulator layout a lane holds one
 // column, so with the transposed problem a lane holds ONE query row: the
-// reference maximum, the running sum and the rescale factor of the online
-// softmax are one scalar per lane, and the exponentiated S^T accumulators are,
-// register for register, the B operand of the second product.  P never touches
-// LDS and is never shuffled between lanes.  The price is that V must sit
-// transposed in LDS; the transpose happens in registers on the way in.
+// softmax reference and the running sum are one scalar per lane, and the
+// exponentiated S^T accumulators are, register for register, the B operand of
+// the second product.  P never touches LDS and is never shuffled between lanes.
 //
 // The contraction index of an MFMA may be permuted freely as long as A and B
 // agree.  For O^T the index is the key position: accumulator register r of lane
 // (g = lane / 32) holds key  8 (r / 4) + 4 g + r % 4  of the 32-key block, so
-// registers 8 m .. 8 m + 7 are fed to MFMA m of the block and V^T is stored in
-// LDS with the key order permuted to match (bits 2 and 3 of the key swapped),
-// which makes the A operand one 16-byte LDS read.
+// registers 8 m .. 8 m + 7 are fed to MFMA m of the block, and the V^T operand
+// is gathered in exactly that key order.
+//
+// Staging.  K and V tiles go from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane, no registers, no LDS store
+// instructions), row-major as they are in memory.  A wave instruction fills
+// 1 KiB of consecutive LDS, so rows cannot be padded; instead the 16-byte chunks
+// of a row are XOR-swizzled by the row number on the way in, each tensor with
+// the pattern that makes its own fragment reads conflict-free.  The K operand is
+// one ds_read_b128 per fragment; the V^T operand is two ds_read_b64_tr_b16:
+// within 16 lanes, lane j receives element j % 4 of the 8-byte chunks addressed
+// by lanes j / 4, j / 4 + 4, j / 4 + 8, j / 4 + 12, i.e. four keys of one channel.
 //
 // A workgroup is QW x KS waves: QW groups of query rows times a KS-way split of
 // every staged key tile.  A wave takes 64 keys of each tile as two 32-key
@@ -29,17 +36,19 @@
 // wave.  With S_X(t) = scores of block X of tile t, the loop body is
 //   phase 1   MFMA: S_Y(t), O += P_Y(t-1) V     | VALU: P_X(t) = exp(S_X(t) - m)
 //   barrier
-//   phase 2   MFMA: O += P_X(t) V, S_X(t+1)     | VALU: P_Y(t) = exp(S_Y(t) - m)
-//             then tile t+2 of K and tile t+1 of V go from registers to LDS and
-//             the global loads of the tiles after them are issued.
+//   phase 2   MFMA: S_X(t+1), O += P_X(t) V     | VALU: P_Y(t) = exp(S_Y(t) - m)
+//             and, first thing after the barrier, the loads of K(t+2) and
+//             V(t+1) into the buffers whose last readers were in phase 1.
 // LDS holds two K tiles and two V tiles; one barrier per tile is enough because
 // a buffer is only overwritten in the phase after its last reader.
 //
-// The reference maximum m is lazy: it is raised (and O, the running sum and the
-// pending P rescaled) only when a block's maximum exceeds it by more than 2^8,
-// which after the first tile practically never happens; exp(S - m) then stays
-// below 2^8, harmless in fp32 and in bf16.  The result does not depend on which
-// reference is used.
+// Softmax reference.  exp(S - m) is exact for ANY per-row reference m as long as
+// nothing overflows, so the fast loop fixes m at the maximum of the row's first
+// visible block and never touches O again: no rescaling, no branch.  Every block
+// maximum is still computed; should one exceed m by more than 2^64 (fp32 would
+// overflow near 2^127) the workgroup raises a flag, throws its result away and
+// redoes its rows with the textbook online softmax in a plain loop.  Real
+// attention logits never get there; adversarial inputs stay correct.
 #include <type_traits>
 
 #include "kvp_internal.h"
@@ -52,19 +61,18 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 constexpr int kThreads = 256;
-constexpr float kLazyLog2 = 8.f;   // raise the reference when a block maximum exceeds it by 2^8
+constexpr float kRedoLog2 = 64.f;   // redo a row tile when a block maximum exceeds the reference by 2^64
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
   f32x2 v = {lo, hi};
   bf16x2 b = __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32, round to nearest even
   return __builtin_bit_cast(unsigned, b);
 }
-__device__ __forceinline__ float bf16_lo(unsigned x) { return __uint_as_float(x << 16); }
-__device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x & 0xFFFF0000u); }
 
 // value of the same row held by the other half of the wave (lane ^ 32)
 __device__ __forceinline__ float max_with_other_half(float x) {
@@ -76,23 +84,32 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+__device__ __forceinline__ bf16x8 lds_read_b128(const u16* p) {
+  return *reinterpret_cast<const bf16x8*>(p);
+}
+// two transposing reads: keys k .. k+3 and k+8 .. k+11 of this lane's channel
+__device__ __forceinline__ bf16x8 lds_read_vt(const u16* p, int eight_rows) {
+  const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(p));
+  const i16x4 hi =
+      __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(p + eight_rows));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 template <int D, int QT, int QW, int KS>
 struct Shape {
   static constexpr int kRows = QW * QT * 32;          // query rows per workgroup
   static constexpr int kTk = KS * 64;                 // keys per staged tile
-  static constexpr int kKStride = D + 8;              // bf16 elements per K row in LDS
-  static constexpr int kVStride = kTk + 8;            // bf16 elements per V^T row in LDS
-  static constexpr int kKTile = kTk * kKStride;       // elements
-  static constexpr int kVTile = D * kVStride;
-  static constexpr int kTileBytes = 2 * (kKTile + kVTile) * 2;   // two buffers each
+  static constexpr int kChunks = D / 8;               // 16-byte chunks per row
+  static constexpr int kRowsPerLoad = 64 / kChunks;   // rows one wave instruction brings in
+  static constexpr int kRowGroup = 4 * kRowsPerLoad;  // rows the four waves bring in per step
+  static constexpr int kLoadsPerWave = kTk / kRowGroup;            // per tensor and tile
+  static constexpr int kTile = kTk * D;               // bf16 elements of a K or V tile, unpadded
+  static constexpr int kTileBytes = 4 * kTile * 2;    // two K and two V buffers
   static constexpr int kMergeFloats = QT * (D / 32) * 16 * 64 + 2 * QT * 64;  // per wave
   static constexpr int kMergeBytes = (KS - 1) * QW * kMergeFloats * 4;
   static constexpr int kLdsBytes = kTileBytes > kMergeBytes ? kTileBytes : kMergeBytes;
-  static constexpr int kKPieces = kTk * (D / 8);      // 16-byte pieces of a K tile
-  static constexpr int kKPer = kKPieces / kThreads;
-  static constexpr int kVGroups = (kTk / 4) * (D / 8);  // 4 keys x 8 channels each
-  static constexpr int kVPer = kVGroups / kThreads;
-  static_assert(kKPieces % kThreads == 0 && kVGroups % kThreads == 0, "tile must split evenly");
+  static_assert(QW * KS == 4, "four waves per workgroup");
+  static_assert(kTk == 128, "the staging map assumes 128-key tiles");
 };
 
 template <int D, int QT, int QW, int KS>
@@ -100,8 +117,8 @@ __global__ void __launch_bounds__(kThreads)
 attention_kernel(const AttnArgs a) {
   using S = Shape<D, QT, QW, KS>;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  u16* const lds_k = reinterpret_cast<u16*>(lds_raw);              // [2][kKTile]
-  u16* const lds_v = lds_k + 2 * S::kKTile;                        // [2][kVTile]
+  u16* const lds_k = reinterpret_cast<u16*>(lds_raw);              // [2][kTile]
+  u16* const lds_v = lds_k + 2 * S::kTile;                         // [2][kTile]
 
   // XCD-aware order: consecutive work items (same KV head) land on one die
   const int xcd = blockIdx.x % kXcds;
@@ -134,329 +151,439 @@ attention_kernel(const AttnArgs a) {
   const u16* kn = a.k_new + (size_t)hk * D;
   const u16* vn = a.v_new + (size_t)hk * D;
   const int new_stride = a.n_kv_heads * D;
-
-  // ---- Q fragments: B operand, lane holds Q[q0 + 32 t + l32][16 s + 8 g .. + 7]
-  bf16x8 qf[QT][D / 16];
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    const int row = q0 + 32 * t + l32;
-    const u16* src = a.q + ((size_t)row * a.n_q_heads + h) * D + 8 * g;
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      u32x4 x = {0u, 0u, 0u, 0u};
-      if (row < n) x = *reinterpret_cast<const u32x4*>(src + 16 * s);
-      qf[t][s] = __builtin_bit_cast(bf16x8, x);
-    }
-  }
-
-  f32x16 o[QT][D / 32];
-  float m_ref[QT], l_run[QT];
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    m_ref[t] = -INFINITY;
-    l_run[t] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[t][dt][r] = 0.f;
-  }
-
-  // ---- staging of key tiles: global -> registers -> LDS
-  // K piece i = tid + 256 j: row i / (D/8), 16-byte column i % (D/8)
-  // V group i = tid + 256 j: keys 4 (i % (Tk/4)) .. + 3, channels 8 (i / (Tk/4)) .. + 7
-  u32x4 kst[S::kKPer];
-  u32x4 vst[S::kVPer][4];
-  const int k_row = tid / (D / 8), k_c8 = tid % (D / 8);
-  constexpr int kKRowStep = kThreads / (D / 8);          // rows between a thread's K pieces
-  const int v_quad = tid % (S::kTk / 4), v_oct = tid / (S::kTk / 4);
-  constexpr int kVOctStep = kThreads / (S::kTk / 4);     // channel octets between a thread's V groups
-
-  auto load_k = [&](int t) __attribute__((always_inline)) {
-    const int base = t * S::kTk;
-    if (base + S::kTk <= c) {
-      const u16* p = kc + (size_t)base * D + k_row * D + 8 * k_c8;
-#pragma unroll
-      for (int j = 0; j < S::kKPer; ++j) kst[j] = *reinterpret_cast<const u32x4*>(p + j * kKRowStep * D);
-    } else if (base >= c && base + S::kTk <= n_cand) {
-      const u16* p = kn + (size_t)(base - c) * new_stride + (size_t)k_row * new_stride + 8 * k_c8;
-#pragma unroll
-      for (int j = 0; j < S::kKPer; ++j)
-        kst[j] = *reinterpret_cast<const u32x4*>(p + (size_t)j * kKRowStep * new_stride);
-    } else {
-#pragma unroll
-      for (int j = 0; j < S::kKPer; ++j) {
-        const int kv = min(base + k_row + j * kKRowStep, n_cand - 1);   // past the end: any finite row
-        const u16* p = kv < c ? kc + (size_t)kv * D : kn + (size_t)(kv - c) * new_stride;
-        kst[j] = *reinterpret_cast<const u32x4*>(p + 8 * k_c8);
-      }
-    }
-  };
-  auto load_v = [&](int t) __attribute__((always_inline)) {
-    const int base = t * S::kTk;
-    if (base + S::kTk <= c) {
-      const u16* p = vc + (size_t)base * D + 4 * v_quad * D + 8 * v_oct;
-#pragma unroll
-      for (int j = 0; j < S::kVPer; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          vst[j][e] = *reinterpret_cast<const u32x4*>(p + e * D + 8 * j * kVOctStep);
-    } else if (base >= c && base + S::kTk <= n_cand) {
-      const u16* p = vn + (size_t)(base - c) * new_stride + (size_t)(4 * v_quad) * new_stride + 8 * v_oct;
-#pragma unroll
-      for (int j = 0; j < S::kVPer; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          vst[j][e] = *reinterpret_cast<const u32x4*>(p + (size_t)e * new_stride + 8 * j * kVOctStep);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int kv = min(base + 4 * v_quad + e, n_cand - 1);
-        const u16* p = (kv < c ? vc + (size_t)kv * D : vn + (size_t)(kv - c) * new_stride) + 8 * v_oct;
-#pragma unroll
-        for (int j = 0; j < S::kVPer; ++j) vst[j][e] = *reinterpret_cast<const u32x4*>(p + 8 * j * kVOctStep);
-      }
-    }
-  };
-  auto store_k = [&](int buf) __attribute__((always_inline)) {
-    u16* kt = lds_k + buf * S::kKTile + k_row * S::kKStride + 8 * k_c8;
-#pragma unroll
-    for (int j = 0; j < S::kKPer; ++j)
-      *reinterpret_cast<u32x4*>(kt + j * kKRowStep * S::kKStride) = kst[j];
-  };
-  auto store_v = [&](int buf) __attribute__((always_inline)) {
-    const int key = 4 * v_quad;
-    // key order inside a 32-key block: swap bits 2 and 3
-    const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);
-    u16* vt = lds_v + buf * S::kVTile + 8 * v_oct * S::kVStride + pos;
-#pragma unroll
-    for (int j = 0; j < S::kVPer; ++j) {
-      const u32x4 r0 = vst[j][0], r1 = vst[j][1], r2 = vst[j][2], r3 = vst[j][3];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int wd = e >> 1;
-        u32x2 col;
-        if ((e & 1) == 0) {
-          col.x = (r0[wd] & 0xFFFFu) | (r1[wd] << 16);
-          col.y = (r2[wd] & 0xFFFFu) | (r3[wd] << 16);
-        } else {
-          col.x = (r0[wd] >> 16) | (r1[wd] & 0xFFFF0000u);
-          col.y = (r2[wd] >> 16) | (r3[wd] & 0xFFFF0000u);
-        }
-        *reinterpret_cast<u32x2*>(vt + (8 * j * kVOctStep + e) * S::kVStride) = col;
-      }
-    }
-  };
-
   const float sl2 = a.scale_log2;
-  const float lazy_raw = kLazyLog2 / sl2;     // the lazy margin in units of the raw dot product
 
-  // S^T block = K[block rows] Q^T, block x in {0 (X), 1 (Y)} of this wave's 64 keys of the tile
-  auto qk = [&](f32x16 (&s)[QT], int kbuf, int x) __attribute__((always_inline)) {
-    const u16* krow = lds_k + kbuf * S::kKTile + (ks * 64 + 32 * x + l32) * S::kKStride + 8 * g;
+  // ---- staging: global -> LDS, 16 bytes per lane, chunks swizzled by row.
+  // Instruction j of wave w brings in rows kRowGroup j + kRowsPerLoad w + (0 .. kRowsPerLoad-1)
+  // of the tile; a lane always handles the same row residue, so its swizzle is a constant.
+  const int ld_sub = lane / S::kChunks, ld_pos = lane % S::kChunks;
+  const int ld_row = S::kRowsPerLoad * wave + ld_sub;          // + kRowGroup j
+  const int ld_chunk_k = ld_pos ^ (ld_row % S::kChunks);
+  const int ld_chunk_v = ld_pos ^ (2 * (ld_row % (S::kChunks / 2)));
+  auto lds_dst = [&](u16* tile, int j) __attribute__((always_inline)) -> u16* {
+    return tile + (S::kRowGroup * j + S::kRowsPerLoad * wave) * D;     // wave-uniform
+  };
+  auto load16 = [&](const u16* src, u16* dst) __attribute__((always_inline)) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+  };
+  // tile t lies entirely in the cache or entirely in the block: one base, one stride
+  auto tile_is_uniform = [&](int t) __attribute__((always_inline)) -> bool {
+    const int base = t * S::kTk;
+    return base + S::kTk <= c || (base >= c && base + S::kTk <= n_cand);
+  };
+  auto issue_uniform = [&](const u16* cache, const u16* fresh, u16* tile, int t, int chunk)
+      __attribute__((always_inline)) {
+    const int base = t * S::kTk;
+    const bool cached = base < c;
+    const int stride = cached ? D : new_stride;
+    const u16* src = (cached ? cache + (size_t)base * D : fresh + (size_t)(base - c) * new_stride) +
+                     ld_row * stride + 8 * chunk;
+#pragma unroll
+    for (int j = 0; j < S::kLoadsPerWave; ++j) load16(src + (size_t)(S::kRowGroup * j) * stride, lds_dst(tile, j));
+  };
+  auto issue_any = [&](const u16* cache, const u16* fresh, u16* tile, int t, int chunk)
+      __attribute__((always_inline)) {
+    const int base = t * S::kTk;
+#pragma unroll
+    for (int j = 0; j < S::kLoadsPerWave; ++j) {
+      const int kv = min(base + S::kRowGroup * j + ld_row, n_cand - 1);   // past the end: any finite row
+      const u16* src = kv < c ? cache + (size_t)kv * D : fresh + (size_t)(kv - c) * new_stride;
+      load16(src + 8 * chunk, lds_dst(tile, j));
+    }
+  };
+
+  // ---- per-lane LDS read offsets (bf16 elements), swizzle folded in
+  // K operand, d-slice st: row (block + l32), chunk (2 st + g) ^ (row % kChunks)
+  int k_off[D / 16];
+  {
+    const int q = g ^ (l32 % S::kChunks);
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) k_off[st] = l32 * D + 8 * ((2 * st) ^ q);
+  }
+  // V^T operand, channel tile dt: this lane addresses key row 4 g + (lane % 16) / 4 (+ block + 16 mm
+  // + 8 h) and the 8-byte half (lane % 4) & 1 of chunk 4 dt + 2 ((lane / 16) % 2) + (lane % 4) / 2
+  int v_off[D / 32];
+  {
+    const int rsub = 4 * g + ((lane & 15) >> 2);
+    const int z = 2 * (rsub % (S::kChunks / 2));
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+      const int chunk = (4 * dt + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ z;
+      v_off[dt] = rsub * D + 8 * chunk + 4 * (lane & 1);
+    }
+  }
+
+  // ================================================================ fast path
+  bool redo = false;
+  {
+    // ---- Q fragments: B operand, lane holds Q[q0 + 32 t + l32][16 s + 8 g .. + 7]
+    bf16x8 qf[QT][D / 16];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      const int row = min(q0 + 32 * t + l32, n - 1);     // rows past the block are computed, not stored
+      const u16* src = a.q + ((size_t)row * a.n_q_heads + h) * D + 8 * g;
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s)
+        qf[t][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + 16 * s));
+    }
+    f32x16 o[QT][D / 32];
+    float m_ref[QT], l_run[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      m_ref[t] = -INFINITY;
+      l_run[t] = 0.f;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[t][dt][r] = 0.f;
+    }
+    const float redo_raw = kRedoLog2 / sl2;       // the margin in units of the raw dot product
+    const int blk_off = 64 * ks * D;               // this wave's 64 keys inside a tile
+
+    // Hide block keys a row may not see, fix the reference at the first visible block, and
+    // watch for a block maximum far above the reference.
+    auto prepare = [&](f32x16 (&s)[QT], int kb, auto mask) __attribute__((always_inline)) {
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        if constexpr (decltype(mask)::value) {
+          // key kb + 8 (r / 4) + 4 g + r % 4 is visible when cached, or a block key not after the row
+          const int lim = min(q0 + 32 * t + l32 + c, n_cand - 1) - kb - 4 * g;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[t][r] = (8 * (r >> 2) + (r & 3) <= lim) ? s[t][r] : -INFINITY;
+        }
+        float v = s[t][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) v = fmaxf(v, s[t][r]);
+        const float mx = max_with_other_half(v);
+        m_ref[t] = (m_ref[t] == -INFINITY) ? mx : m_ref[t];
+        redo |= mx > m_ref[t] + redo_raw;
+      }
+    };
+
+    // One phase, as one basic block: MFMA i is followed by the exponentials of 128 / D elements
+    // of the S block computed in the previous phase, and LDS fragment reads run kAhead operands
+    // ahead of their use.  The scheduling-group barriers at the end ask the machine scheduler for
+    // exactly this interleaving.
+    //   s_exp -> p_out   P = exp2((S - m) * scale) for the block whose scores are ready
+    //   s_new            S^T of the next block = K[kt rows] Q^T
+    //   p_pend, vt       O^T += V^T P^T for the block exponentiated one phase ago
+    auto phase_core = [&](const f32x16 (&s_exp)[QT], unsigned (&p_out)[QT][8], f32x16 (&s_new)[QT],
+                          const u16* kt, const unsigned (&p_pend)[QT][8], const u16* vt)
+        __attribute__((always_inline)) {
+      constexpr int kNK = D / 16;            // K fragments
+      constexpr int kNV = (D / 32) * 2;      // V^T fragments
+      constexpr int kAhead = D / 32;
+      constexpr int kPerMfma = 128 / D;      // elements exponentiated per MFMA
+      float neg[QT], sum[QT], held[QT];
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        const float m_use = (m_ref[t] == -INFINITY) ? 0.f : m_ref[t];   // row has seen nothing yet
+        neg[t] = -m_use * sl2;
+        sum[t] = 0.f;
+        held[t] = 0.f;
+      }
+      bf16x8 kfr[kNK], vfr[kNV];
+      auto read_k = [&](int st) __attribute__((always_inline)) { kfr[st] = lds_read_b128(kt + k_off[st]); };
+      auto read_v = [&](int vi) __attribute__((always_inline)) {
+        vfr[vi] = lds_read_vt(vt + v_off[vi / 2] + 16 * (vi % 2) * D, 8 * D);
+      };
+      int ei = 0;   // next element to exponentiate
+      auto exp_some = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kPerMfma; ++k, ++ei) {
+          const int t = ei / 16, r = ei % 16;
+          const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s_exp[t][r], sl2, neg[t]));
+          sum[t] += pe;
+          if (r & 1) p_out[t][r >> 1] = pack_bf16(held[t], pe); else held[t] = pe;
+        }
+      };
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int st = 0; st < kAhead; ++st) read_k(st);
+#pragma unroll
+      for (int st = 0; st < kNK; ++st) {
+        if (st + kAhead < kNK) read_k(st + kAhead);
+        else read_v(st + kAhead - kNK);
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+          s_new[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[st], qf[t][st], st == 0 ? zero : s_new[t], 0, 0, 0);
+          exp_some();
+        }
+      }
+#pragma unroll
+      for (int vi = 0; vi < kNV; ++vi) {
+        if (vi + kAhead < kNV) read_v(vi + kAhead);
+        const int dt = vi / 2, mm = vi % 2;
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+          const u32x4 pw = {p_pend[t][4 * mm], p_pend[t][4 * mm + 1], p_pend[t][4 * mm + 2], p_pend[t][4 * mm + 3]};
+          o[t][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[vi], __builtin_bit_cast(bf16x8, pw), o[t][dt], 0, 0, 0);
+          exp_some();
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < QT; ++t) l_run[t] += sum[t];
+      // pipeline: one MFMA, one LDS read while any remain, then the vector work of its elements
+      constexpr int kMfmas = QT * (kNK + kNV);
+      constexpr int kReads = kNK + 2 * kNV - kAhead;      // the first kAhead reads go ahead of everything
+#pragma unroll
+      for (int i = 0; i < kMfmas; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
+        if (i < kReads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // LDS read
+        __builtin_amdgcn_sched_group_barrier(0x002, 5 * kPerMfma, 0);           // VALU (incl. exp)
+      }
+    };
+
+    // ---- prologue: K(0), K(1), V(0) into LDS, S_X(0) computed
+    f32x16 sx[QT], sy[QT];
+    unsigned px[QT][8], py[QT][8];
 #pragma unroll
     for (int t = 0; t < QT; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
-#pragma unroll
-    for (int st = 0; st < D / 16; ++st) {
-      const bf16x8 ka = *reinterpret_cast<const bf16x8*>(krow + 16 * st);
+      for (int r = 0; r < 8; ++r) { px[t][r] = 0u; py[t][r] = 0u; }
+    issue_any(kc, kn, lds_k, 0, ld_chunk_k);
+    issue_any(vc, vn, lds_v, 0, ld_chunk_v);
+    issue_any(kc, kn, lds_k + S::kTile, 1, ld_chunk_k);
+    // V buffer 1 is read as "V(-1)" with P = 0 in the first phase: make it finite
+    for (int i = tid; i < S::kTile / 8; i += kThreads)
+      reinterpret_cast<u32x4*>(lds_v + S::kTile)[i] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();     // waits for this wave's loads, then for everybody's
+    {
+      // S_X(0) without anything to overlap with
 #pragma unroll
       for (int t = 0; t < QT; ++t)
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[t][st], s[t], 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sx[t][r] = 0.f;
+#pragma unroll
+      for (int st = 0; st < D / 16; ++st) {
+        const bf16x8 ka = lds_read_b128(lds_k + blk_off + k_off[st]);
+#pragma unroll
+        for (int t = 0; t < QT; ++t) sx[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[t][st], sx[t], 0, 0, 0);
+      }
     }
-  };
-  // O^T += V^T[block] P^T
-  auto pv = [&](const unsigned (&pb)[QT][8], int vbuf, int x) __attribute__((always_inline)) {
-    const u16* vrow = lds_v + vbuf * S::kVTile + l32 * S::kVStride + ks * 64 + 32 * x + 8 * g;
+
+    // kTag = t & 1 as a compile-time constant in the steady-state loop, -1 for "use t & 1".
+    // The steady-state loop also knows that the tiles it prefetches are uniform.
+    auto body = [&](int t, auto buf_tag, auto mask) __attribute__((always_inline)) {
+      constexpr int kTag = decltype(buf_tag)::value;
+      const int buf = kTag >= 0 ? kTag : (t & 1);
+      const int kb = t * S::kTk + ks * 64;
+      u16* k_cur = lds_k + buf * S::kTile;
+      u16* k_nxt = lds_k + (buf ^ 1) * S::kTile;
+      u16* v_cur = lds_v + buf * S::kTile;
+      u16* v_prv = lds_v + (buf ^ 1) * S::kTile;
+      // ---- phase 1: P_X(t), S_Y(t), O += P_Y(t-1) V(t-1)
+      prepare(sx, kb, mask);
+      phase_core(sx, px, sy, k_cur + blk_off + 32 * D, py, v_prv + blk_off + 32 * D);
+      __syncthreads();            // also waits for the loads this wave issued in the last phase 2
+      // ---- phase 2: P_Y(t), S_X(t+1), O += P_X(t) V(t)
+      if (kTag >= 0) {
+        issue_uniform(kc, kn, k_cur, t + 2, ld_chunk_k);
+        issue_uniform(vc, vn, v_prv, t + 1, ld_chunk_v);
+      } else {
+        issue_any(kc, kn, k_cur, t + 2, ld_chunk_k);
+        issue_any(vc, vn, v_prv, t + 1, ld_chunk_v);
+      }
+      prepare(sy, kb + 32, mask);
+      phase_core(sy, py, sx, k_nxt + blk_off, px, v_cur + blk_off);
+    };
+    typedef std::integral_constant<int, 0> Even;
+    typedef std::integral_constant<int, 1> Odd;
+    typedef std::integral_constant<int, -1> Any;
+    // steady state: tiles t, t+1 plain and tiles t+1 .. t+3 uniform
+    int n_fast = 0;
+    while (n_fast + 1 < n_plain && tile_is_uniform(n_fast + 1) && tile_is_uniform(n_fast + 2) &&
+           tile_is_uniform(n_fast + 3))
+      n_fast += 2;
+    int t = 0;
+    for (; t < n_fast; t += 2) {
+      body(t, Even{}, std::false_type{});
+      body(t + 1, Odd{}, std::false_type{});
+    }
+    for (; t < n_tiles; ++t) body(t, Any{}, std::true_type{});   // masking a fully visible tile is harmless
+    __syncthreads();               // V of the last tile has landed for everybody
+    {
+      // O += P_Y V of the last tile
+      const u16* vt = lds_v + ((n_tiles + 1) & 1) * S::kTile + blk_off + 32 * D;
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt) {
+      for (int vi = 0; vi < (D / 32) * 2; ++vi) {
+        const int dt = vi / 2, mm = vi % 2;
+        const bf16x8 va = lds_read_vt(vt + v_off[dt] + 16 * mm * D, 8 * D);
 #pragma unroll
-      for (int mm = 0; mm < 2; ++mm) {
-        const bf16x8 va = *reinterpret_cast<const bf16x8*>(vrow + dt * 32 * S::kVStride + 16 * mm);
-#pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          const u32x4 px = {pb[t][4 * mm], pb[t][4 * mm + 1], pb[t][4 * mm + 2], pb[t][4 * mm + 3]};
-          o[t][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, px), o[t][dt], 0, 0, 0);
+        for (int tq = 0; tq < QT; ++tq) {
+          const u32x4 pw = {py[tq][4 * mm], py[tq][4 * mm + 1], py[tq][4 * mm + 2], py[tq][4 * mm + 3]};
+          o[tq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, pw), o[tq][dt], 0, 0, 0);
         }
       }
     }
-  };
-  // Hide block keys a row may not see, then decide whether the reference maximum must rise.
-  // `pend` is the P block that has been computed against the old reference but not yet
-  // multiplied into O: it is rescaled together with O.
-  auto prepare = [&](f32x16 (&s)[QT], unsigned (&pend)[QT][8], int kb, auto mask) __attribute__((always_inline)) {
-    if constexpr (decltype(mask)::value) {
-#pragma unroll
-      for (int t = 0; t < QT; ++t) {
-        // key kb + 8 (r / 4) + 4 g + r % 4 is visible when it is cached, or a block key not after the row
-        const int lim = min(q0 + 32 * t + l32 + c, n_cand - 1) - kb - 4 * g;   // visible iff 8 (r/4) + r%4 <= lim
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[t][r] = (8 * (r >> 2) + (r & 3) <= lim) ? s[t][r] : -INFINITY;
-      }
-    }
-    float mx[QT];
-    bool raise = false;
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      float v = s[t][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) v = fmaxf(v, s[t][r]);
-      mx[t] = max_with_other_half(v);
-      raise |= mx[t] > m_ref[t] + lazy_raw;     // also true for the first visible key (m_ref = -inf)
-    }
-    if (__any(raise)) {
-#pragma unroll
-      for (int t = 0; t < QT; ++t) {
-        const bool up = mx[t] > m_ref[t] + lazy_raw;
-        const float m_new = up ? mx[t] : m_ref[t];
-        const float alpha = up ? __builtin_amdgcn_exp2f((m_ref[t] - m_new) * sl2) : 1.f;
-        m_ref[t] = m_new;
-        l_run[t] *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[t][dt][r] *= alpha;
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-          pend[t][r] = pack_bf16(bf16_lo(pend[t][r]) * alpha, bf16_hi(pend[t][r]) * alpha);
-      }
-    }
-  };
-  // P = exp2((S - m) * scale): the part that overlaps with the matrix work
-  auto exponentiate = [&](const f32x16 (&s)[QT], unsigned (&pb)[QT][8]) __attribute__((always_inline)) {
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      const float m_use = (m_ref[t] == -INFINITY) ? 0.f : m_ref[t];   // row has seen nothing yet
-      const float neg = -m_use * sl2;
-      float sum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][2 * r], sl2, neg));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][2 * r + 1], sl2, neg));
-        sum += p0 + p1;
-        pb[t][r] = pack_bf16(p0, p1);
-      }
-      l_run[t] += sum;
-    }
-  };
+    redo = __syncthreads_or(redo) != 0;     // workgroup-uniform; also: everybody is done with the tiles
 
-  // ---- prologue: K(0), K(1), V(0) in LDS, K(2), V(1) in registers, S_X(0) computed
-  f32x16 sx[QT], sy[QT];
-  unsigned px[QT][8], py[QT][8];
+    if (!redo) {
+      // lanes l and l + 32 each summed half of the keys of a row
 #pragma unroll
-  for (int t = 0; t < QT; ++t)
+      for (int tq = 0; tq < QT; ++tq) l_run[tq] = sum_with_other_half(l_run[tq]);
+      // ---- merge the KS partial results of every row through LDS
+      if (KS > 1) {
+        float* mrg = reinterpret_cast<float*>(lds_raw);
+        if (ks > 0) {
+          float* mine = mrg + (size_t)((ks - 1) * QW + qw) * S::kMergeFloats;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) { px[t][r] = 0u; py[t][r] = 0u; }
-  load_k(0);
-  load_v(0);
-  store_k(0);
-  store_v(0);
-  load_k(1);
-  // V buffer 1 is read as "V(-1)" with P = 0 in the first phase: make it finite
-  for (int i = tid; i < S::kVTile / 8; i += kThreads)
-    reinterpret_cast<u32x4*>(lds_v + S::kVTile)[i] = u32x4{0u, 0u, 0u, 0u};
-  store_k(1);
-  load_k(2);
-  load_v(1);
-  __syncthreads();
-  qk(sx, 0, 0);
-
-  auto body = [&](int t, auto mask) __attribute__((always_inline)) {
-    const int kb = t * S::kTk + ks * 64;
-    // ---- phase 1
-    prepare(sx, py, kb, mask);
-    qk(sy, t & 1, 1);
-    pv(py, (t + 1) & 1, 1);
-    exponentiate(sx, px);
-    __syncthreads();
-    // ---- phase 2
-    prepare(sy, px, kb + 32, mask);
-    pv(px, t & 1, 0);
-    qk(sx, (t + 1) & 1, 0);
-    exponentiate(sy, py);
-    store_k(t & 1);            // K(t+2)
-    store_v((t + 1) & 1);      // V(t+1)
-    load_k(t + 3);
-    load_v(t + 2);
-  };
-  for (int t = 0; t < n_plain; ++t) body(t, std::false_type{});
-  for (int t = n_plain; t < n_tiles; ++t) body(t, std::true_type{});
-  __syncthreads();
-  pv(py, (n_tiles + 1) & 1, 1);   // P_Y of the last tile
-
-  // lanes l and l + 32 each summed half of the keys of a row
+          for (int tq = 0; tq < QT; ++tq) {
 #pragma unroll
-  for (int t = 0; t < QT; ++t) l_run[t] = sum_with_other_half(l_run[t]);
-
-  // ---- merge the KS partial results of every row through LDS
-  if (KS > 1) {
-    float* mrg = reinterpret_cast<float*>(lds_raw);
-    __syncthreads();   // everybody is done with the tiles
-    if (ks > 0) {
-      float* mine = mrg + (size_t)((ks - 1) * QW + qw) * S::kMergeFloats;
+            for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int t = 0; t < QT; ++t) {
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            mine[((t * (D / 32) + dt) * 16 + r) * 64 + lane] = o[t][dt][r];
-        mine[QT * (D / 32) * 16 * 64 + t * 64 + lane] = m_ref[t];
-        mine[QT * (D / 32) * 16 * 64 + (QT + t) * 64 + lane] = l_run[t];
-      }
-    }
-    __syncthreads();
-    if (ks == 0) {
-#pragma unroll
-      for (int t = 0; t < QT; ++t) {
-        float mt = m_ref[t];
-        for (int s2 = 1; s2 < KS; ++s2) {
-          const float* other = mrg + (size_t)((s2 - 1) * QW + qw) * S::kMergeFloats;
-          mt = fmaxf(mt, other[QT * (D / 32) * 16 * 64 + t * 64 + lane]);
+              for (int r = 0; r < 16; ++r)
+                mine[((tq * (D / 32) + dt) * 16 + r) * 64 + lane] = o[tq][dt][r];
+            mine[QT * (D / 32) * 16 * 64 + tq * 64 + lane] = m_ref[tq];
+            mine[QT * (D / 32) * 16 * 64 + (QT + tq) * 64 + lane] = l_run[tq];
+          }
         }
-        const float m_use = (mt == -INFINITY) ? 0.f : mt;
-        const float f0 = __builtin_amdgcn_exp2f((m_ref[t] - m_use) * sl2);
-        l_run[t] *= f0;
+        __syncthreads();
+        if (ks == 0) {
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+          for (int tq = 0; tq < QT; ++tq) {
+            float mt = m_ref[tq];
+            for (int s2 = 1; s2 < KS; ++s2) {
+              const float* other = mrg + (size_t)((s2 - 1) * QW + qw) * S::kMergeFloats;
+              mt = fmaxf(mt, other[QT * (D / 32) * 16 * 64 + tq * 64 + lane]);
+            }
+            const float m_use = (mt == -INFINITY) ? 0.f : mt;
+            const float f0 = __builtin_amdgcn_exp2f((m_ref[tq] - m_use) * sl2);
+            l_run[tq] *= f0;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) o[t][dt][r] *= f0;
-        for (int s2 = 1; s2 < KS; ++s2) {
-          const float* other = mrg + (size_t)((s2 - 1) * QW + qw) * S::kMergeFloats;
-          const float ms = other[QT * (D / 32) * 16 * 64 + t * 64 + lane];
-          const float ls = other[QT * (D / 32) * 16 * 64 + (QT + t) * 64 + lane];
-          const float fs = __builtin_amdgcn_exp2f((ms - m_use) * sl2);
-          l_run[t] += ls * fs;
+            for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-          for (int dt = 0; dt < D / 32; ++dt)
+              for (int r = 0; r < 16; ++r) o[tq][dt][r] *= f0;
+            for (int s2 = 1; s2 < KS; ++s2) {
+              const float* other = mrg + (size_t)((s2 - 1) * QW + qw) * S::kMergeFloats;
+              const float ms = other[QT * (D / 32) * 16 * 64 + tq * 64 + lane];
+              const float ls = other[QT * (D / 32) * 16 * 64 + (QT + tq) * 64 + lane];
+              const float fs = __builtin_amdgcn_exp2f((ms - m_use) * sl2);
+              l_run[tq] += ls * fs;
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-              o[t][dt][r] += fs * other[((t * (D / 32) + dt) * 16 + r) * 64 + lane];
+              for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                  o[tq][dt][r] += fs * other[((tq * (D / 32) + dt) * 16 + r) * 64 + lane];
+            }
+            m_ref[tq] = mt;
+          }
         }
-        m_ref[t] = mt;
       }
+      // ---- normalise and store; lane holds O[row][32 dt + 8 j + 4 g + 0..3]
+      if (ks == 0) {
+#pragma unroll
+        for (int tq = 0; tq < QT; ++tq) {
+          const int row = q0 + 32 * tq + l32;
+          if (row < n) {
+            const float inv = 1.f / l_run[tq];
+            u16* dstp = a.out + ((size_t)row * a.n_q_heads + h) * D + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                u32x2 pk;
+                pk.x = pack_bf16(o[tq][dt][4 * j] * inv, o[tq][dt][4 * j + 1] * inv);
+                pk.y = pack_bf16(o[tq][dt][4 * j + 2] * inv, o[tq][dt][4 * j + 3] * inv);
+                *reinterpret_cast<u32x2*>(dstp + 32 * dt + 8 * j) = pk;
+              }
+            if (g == 0)
+              a.lse2[(size_t)h * a.lse_stride + row] = m_ref[tq] * sl2 + __builtin_log2f(l_run[tq]);
+          }
+        }
+      }
+      return;
     }
   }
 
-  // ---- normalise and store; lane holds O[row][32 dt + 8 j + 4 g + 0..3]
-  if (ks == 0) {
+  // ================================================================ careful path
+  // Textbook online softmax, one 32-row tile per wave, one tile buffer, no overlap.
+  // Only reached when a logit exceeded its row's reference by more than 2^64.
+  {
+    const bool active = wave < S::kRows / 32;
+    const int qs = row0 + 32 * wave;
+    bf16x8 qf[D / 16];
+    {
+      const int row = min(qs + l32, n - 1);
+      const u16* src = a.q + ((size_t)row * a.n_q_heads + h) * D + 8 * g;
 #pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      const int row = q0 + 32 * t + l32;
+      for (int s = 0; s < D / 16; ++s)
+        qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + 16 * s));
+    }
+    f32x16 o[D / 32];
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    for (int t = 0; t < n_tiles; ++t) {
+      __syncthreads();                                   // the tile buffer is free
+      issue_any(kc, kn, lds_k, t, ld_chunk_k);
+      issue_any(vc, vn, lds_v, t, ld_chunk_v);
+      __syncthreads();                                   // and full again
+      if (!active) continue;
+      for (int blk = 0; blk < S::kTk / 32; ++blk) {
+        const int kb = t * S::kTk + 32 * blk;
+        if (kb >= n_cand || (kb >= c && kb - c > qs + 31)) continue;    // nothing visible
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int st = 0; st < D / 16; ++st)
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_read_b128(lds_k + 32 * blk * D + k_off[st]), qf[st], s, 0, 0, 0);
+        const int lim = min(qs + l32 + c, n_cand - 1) - kb - 4 * g;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          s[r] = (8 * (r >> 2) + (r & 3) <= lim) ? s[r] : -INFINITY;
+          mx = fmaxf(mx, s[r]);
+        }
+        mx = max_with_other_half(mx);
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
+        const float neg = -m_use * sl2;
+        unsigned pb[8];
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * r], sl2, neg));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * r + 1], sl2, neg));
+          sum += p0 + p1;
+          pb[r] = pack_bf16(p0, p1);
+        }
+        l_run = l_run * alpha + sum;
+        m_run = m_new;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+#pragma unroll
+          for (int mm = 0; mm < 2; ++mm) {
+            const bf16x8 va = lds_read_vt(lds_v + 32 * blk * D + v_off[dt] + 16 * mm * D, 8 * D);
+            const u32x4 pw = {pb[4 * mm], pb[4 * mm + 1], pb[4 * mm + 2], pb[4 * mm + 3]};
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, pw), o[dt], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (active) {
+      l_run = sum_with_other_half(l_run);
+      const int row = qs + l32;
       if (row < n) {
-        const float inv = 1.f / l_run[t];
+        const float inv = 1.f / l_run;
         u16* dstp = a.out + ((size_t)row * a.n_q_heads + h) * D + 4 * g;
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             u32x2 pk;
-            pk.x = pack_bf16(o[t][dt][4 * j] * inv, o[t][dt][4 * j + 1] * inv);
-            pk.y = pack_bf16(o[t][dt][4 * j + 2] * inv, o[t][dt][4 * j + 3] * inv);
+            pk.x = pack_bf16(o[dt][4 * j] * inv, o[dt][4 * j + 1] * inv);
+            pk.y = pack_bf16(o[dt][4 * j + 2] * inv, o[dt][4 * j + 3] * inv);
             *reinterpret_cast<u32x2*>(dstp + 32 * dt + 8 * j) = pk;
           }
-        if (g == 0)
-          a.lse2[(size_t)h * a.lse_stride + row] = m_ref[t] * sl2 + __builtin_log2f(l_run[t]);
+        if (g == 0) a.lse2[(size_t)h * a.lse_stride + row] = m_run * sl2 + __builtin_log2f(l_run);
       }
     }
   }
