@@ -52,7 +52,8 @@ enum { KVP_TEXT = 0, KVP_VISUAL = 1 };
 /* limits */
 enum {
   KVP_MAX_CANDIDATES = 8192,  /* budget + chunk_max may not exceed this        */
-  KVP_MAX_SEGMENTS = 64
+  KVP_MAX_SEGMENTS = 64,
+  KVP_MAX_TOKENS = 1 << 24    /* longest prefix, in tokens                     */
 };
 
 /* One run of consecutive prefix tokens.  Segments must cover [0, N) in order

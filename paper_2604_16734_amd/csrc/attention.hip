@@ -30,10 +30,13 @@
 // every staged key tile.  A wave takes 64 keys of each tile as two 32-key
 // blocks X and Y; the KS partial results of a row are merged through LDS at the
 // end.  The split keeps all 1024 SIMDs busy when a block of the prefix has
-// fewer than 1024 wave-sized row tiles.
+// fewer than 1024 wave-sized row tiles.  Three shapes are built: 2 x 2 waves of
+// 64 rows (one wave per SIMD, 512 registers), 4 x 2 waves of 32 rows (two waves
+// per SIMD, 256 registers each; the fastest on the large shapes) and 2 x 2 waves
+// of 32 rows for blocks too small to fill the chip with 128-row workgroups.
 //
-// Schedule.  One wave per SIMD, so matrix and vector work overlap inside the
-// wave.  With S_X(t) = scores of block X of tile t, the loop body is
+// Schedule.  Matrix and vector work of one wave are made to overlap in program
+// order.  With S_X(t) = scores of block X of tile t, the loop body is
 //   phase 1   MFMA: S_Y(t), O += P_Y(t-1) V     | VALU: P_X(t) = exp(S_X(t) - m)
 //   barrier
 //   phase 2   MFMA: S_X(t+1), O += P_X(t) V     | VALU: P_Y(t) = exp(S_Y(t) - m)
@@ -49,6 +52,7 @@
 // overflow near 2^127) the workgroup raises a flag, throws its result away and
 // redoes its rows with the textbook online softmax in a plain loop.  Real
 // attention logits never get there; adversarial inputs stay correct.
+#include <cstdlib>
 #include <type_traits>
 
 #include "kvp_internal.h"
@@ -65,7 +69,6 @@ typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int kThreads = 256;
 constexpr float kRedoLog2 = 64.f;   // redo a row tile when a block maximum exceeds the reference by 2^64
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
@@ -97,25 +100,28 @@ __device__ __forceinline__ bf16x8 lds_read_vt(const u16* p, int eight_rows) {
 
 template <int D, int QT, int QW, int KS>
 struct Shape {
+  static constexpr int kWaves = QW * KS;
+  static constexpr int kThreads = 64 * kWaves;
   static constexpr int kRows = QW * QT * 32;          // query rows per workgroup
   static constexpr int kTk = KS * 64;                 // keys per staged tile
   static constexpr int kChunks = D / 8;               // 16-byte chunks per row
   static constexpr int kRowsPerLoad = 64 / kChunks;   // rows one wave instruction brings in
-  static constexpr int kRowGroup = 4 * kRowsPerLoad;  // rows the four waves bring in per step
+  static constexpr int kRowGroup = kWaves * kRowsPerLoad;  // rows the waves bring in per step
   static constexpr int kLoadsPerWave = kTk / kRowGroup;            // per tensor and tile
   static constexpr int kTile = kTk * D;               // bf16 elements of a K or V tile, unpadded
   static constexpr int kTileBytes = 4 * kTile * 2;    // two K and two V buffers
   static constexpr int kMergeFloats = QT * (D / 32) * 16 * 64 + 2 * QT * 64;  // per wave
   static constexpr int kMergeBytes = (KS - 1) * QW * kMergeFloats * 4;
   static constexpr int kLdsBytes = kTileBytes > kMergeBytes ? kTileBytes : kMergeBytes;
-  static_assert(QW * KS == 4, "four waves per workgroup");
+  static_assert(kWaves == 4 || kWaves == 8, "four or eight waves per workgroup");
   static_assert(kTk == 128, "the staging map assumes 128-key tiles");
 };
 
 template <int D, int QT, int QW, int KS>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__((Shape<D, QT, QW, KS>::kThreads))
 attention_kernel(const AttnArgs a) {
   using S = Shape<D, QT, QW, KS>;
+  constexpr int kThreads = S::kThreads;
   extern __shared__ __align__(16) unsigned char lds_raw[];
   u16* const lds_k = reinterpret_cast<u16*>(lds_raw);              // [2][kTile]
   u16* const lds_v = lds_k + 2 * S::kTile;                         // [2][kTile]
@@ -163,34 +169,42 @@ attention_kernel(const AttnArgs a) {
   auto lds_dst = [&](u16* tile, int j) __attribute__((always_inline)) -> u16* {
     return tile + (S::kRowGroup * j + S::kRowsPerLoad * wave) * D;     // wave-uniform
   };
+  // Issued as inline assembly on purpose: the compiler then does not know that these loads write
+  // LDS and does not make every later LDS read wait for them.  Ordering is this kernel's job:
+  // wait_loads() before the barrier that publishes a tile.
   auto load16 = [&](const u16* src, u16* dst) __attribute__((always_inline)) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    const unsigned lds_addr =
+        __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) void*)dst);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr)
+                 : "m0", "memory");
+  };
+  auto wait_loads = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), nothing else
   };
   // tile t lies entirely in the cache or entirely in the block: one base, one stride
   auto tile_is_uniform = [&](int t) __attribute__((always_inline)) -> bool {
     const int base = t * S::kTk;
     return base + S::kTk <= c || (base >= c && base + S::kTk <= n_cand);
   };
-  auto issue_uniform = [&](const u16* cache, const u16* fresh, u16* tile, int t, int chunk)
-      __attribute__((always_inline)) {
+  // one instruction (number j) of a uniform tile: src0 is this lane's address for j = 0
+  auto uniform_src = [&](const u16* cache, const u16* fresh, int t, int chunk, int& stride)
+      __attribute__((always_inline)) -> const u16* {
     const int base = t * S::kTk;
     const bool cached = base < c;
-    const int stride = cached ? D : new_stride;
-    const u16* src = (cached ? cache + (size_t)base * D : fresh + (size_t)(base - c) * new_stride) +
-                     ld_row * stride + 8 * chunk;
-#pragma unroll
-    for (int j = 0; j < S::kLoadsPerWave; ++j) load16(src + (size_t)(S::kRowGroup * j) * stride, lds_dst(tile, j));
+    stride = cached ? D : new_stride;
+    return (cached ? cache + (size_t)base * D : fresh + (size_t)(base - c) * new_stride) + ld_row * stride +
+           8 * chunk;
+  };
+  auto issue_any_one = [&](const u16* cache, const u16* fresh, u16* tile, int t, int chunk, int j)
+      __attribute__((always_inline)) {
+    const int kv = min(t * S::kTk + S::kRowGroup * j + ld_row, n_cand - 1);   // past the end: any finite row
+    const u16* src = kv < c ? cache + (size_t)kv * D : fresh + (size_t)(kv - c) * new_stride;
+    load16(src + 8 * chunk, lds_dst(tile, j));
   };
   auto issue_any = [&](const u16* cache, const u16* fresh, u16* tile, int t, int chunk)
       __attribute__((always_inline)) {
-    const int base = t * S::kTk;
 #pragma unroll
-    for (int j = 0; j < S::kLoadsPerWave; ++j) {
-      const int kv = min(base + S::kRowGroup * j + ld_row, n_cand - 1);   // past the end: any finite row
-      const u16* src = kv < c ? cache + (size_t)kv * D : fresh + (size_t)(kv - c) * new_stride;
-      load16(src + 8 * chunk, lds_dst(tile, j));
-    }
+    for (int j = 0; j < S::kLoadsPerWave; ++j) issue_any_one(cache, fresh, tile, t, chunk, j);
   };
 
   // ---- per-lane LDS read offsets (bf16 elements), swizzle folded in
@@ -269,7 +283,7 @@ attention_kernel(const AttnArgs a) {
     //   s_new            S^T of the next block = K[kt rows] Q^T
     //   p_pend, vt       O^T += V^T P^T for the block exponentiated one phase ago
     auto phase_core = [&](const f32x16 (&s_exp)[QT], unsigned (&p_out)[QT][8], f32x16 (&s_new)[QT],
-                          const u16* kt, const unsigned (&p_pend)[QT][8], const u16* vt)
+                          const u16* kt, const unsigned (&p_pend)[QT][8], const u16* vt, auto&& after_mfma)
         __attribute__((always_inline)) {
       constexpr int kNK = D / 16;            // K fragments
       constexpr int kNV = (D / 32) * 2;      // V^T fragments
@@ -309,6 +323,7 @@ attention_kernel(const AttnArgs a) {
         for (int t = 0; t < QT; ++t) {
           s_new[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[st], qf[t][st], st == 0 ? zero : s_new[t], 0, 0, 0);
           exp_some();
+          after_mfma(std::integral_constant<int, 0>{}, st * QT + t);
         }
       }
 #pragma unroll
@@ -320,6 +335,7 @@ attention_kernel(const AttnArgs a) {
           const u32x4 pw = {p_pend[t][4 * mm], p_pend[t][4 * mm + 1], p_pend[t][4 * mm + 2], p_pend[t][4 * mm + 3]};
           o[t][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[vi], __builtin_bit_cast(bf16x8, pw), o[t][dt], 0, 0, 0);
           exp_some();
+          after_mfma(std::integral_constant<int, 1>{}, vi * QT + t);
         }
       }
 #pragma unroll
@@ -348,7 +364,8 @@ attention_kernel(const AttnArgs a) {
     // V buffer 1 is read as "V(-1)" with P = 0 in the first phase: make it finite
     for (int i = tid; i < S::kTile / 8; i += kThreads)
       reinterpret_cast<u32x4*>(lds_v + S::kTile)[i] = u32x4{0u, 0u, 0u, 0u};
-    __syncthreads();     // waits for this wave's loads, then for everybody's
+    wait_loads();
+    __syncthreads();
     {
       // S_X(0) without anything to overlap with
 #pragma unroll
@@ -375,18 +392,33 @@ attention_kernel(const AttnArgs a) {
       u16* v_prv = lds_v + (buf ^ 1) * S::kTile;
       // ---- phase 1: P_X(t), S_Y(t), O += P_Y(t-1) V(t-1)
       prepare(sx, kb, mask);
-      phase_core(sx, px, sy, k_cur + blk_off + 32 * D, py, v_prv + blk_off + 32 * D);
-      __syncthreads();            // also waits for the loads this wave issued in the last phase 2
-      // ---- phase 2: P_Y(t), S_X(t+1), O += P_X(t) V(t)
-      if (kTag >= 0) {
-        issue_uniform(kc, kn, k_cur, t + 2, ld_chunk_k);
-        issue_uniform(vc, vn, v_prv, t + 1, ld_chunk_v);
-      } else {
-        issue_any(kc, kn, k_cur, t + 2, ld_chunk_k);
-        issue_any(vc, vn, v_prv, t + 1, ld_chunk_v);
-      }
+      phase_core(sx, px, sy, k_cur + blk_off + 32 * D, py, v_prv + blk_off + 32 * D, [](auto, int) {});
+      wait_loads();               // the loads this wave issued in the last phase 2 have landed
+      __syncthreads();
+      // ---- phase 2: P_Y(t), S_X(t+1), O += P_X(t) V(t); the loads of K(t+2) and V(t+1) are spread
+      // over the matrix instructions so that their issue does not stall the wave in one burst
       prepare(sy, kb + 32, mask);
-      phase_core(sy, py, sx, k_nxt + blk_off, px, v_cur + blk_off);
+      constexpr int kPerHalf = QT * (D / 16);              // MFMAs in each half of a phase
+      constexpr int kEvery = kPerHalf / S::kLoadsPerWave;  // one load every kEvery MFMAs
+      static_assert(kEvery >= 1 && kPerHalf % S::kLoadsPerWave == 0, "loads must fit the phase");
+      if (kTag >= 0) {
+        int k_stride, v_stride;
+        const u16* k_src = uniform_src(kc, kn, t + 2, ld_chunk_k, k_stride);
+        const u16* v_src = uniform_src(vc, vn, t + 1, ld_chunk_v, v_stride);
+        phase_core(sy, py, sx, k_nxt + blk_off, px, v_cur + blk_off, [&](auto half, int i) __attribute__((always_inline)) {
+          if (i % kEvery != 0) return;
+          const int j = i / kEvery;
+          if (decltype(half)::value == 0) load16(k_src + (size_t)(S::kRowGroup * j) * k_stride, lds_dst(k_cur, j));
+          else load16(v_src + (size_t)(S::kRowGroup * j) * v_stride, lds_dst(v_prv, j));
+        });
+      } else {
+        phase_core(sy, py, sx, k_nxt + blk_off, px, v_cur + blk_off, [&](auto half, int i) __attribute__((always_inline)) {
+          if (i % kEvery != 0) return;
+          const int j = i / kEvery;
+          if (decltype(half)::value == 0) issue_any_one(kc, kn, k_cur, t + 2, ld_chunk_k, j);
+          else issue_any_one(vc, vn, v_prv, t + 1, ld_chunk_v, j);
+        });
+      }
     };
     typedef std::integral_constant<int, 0> Even;
     typedef std::integral_constant<int, 1> Odd;
@@ -402,6 +434,7 @@ attention_kernel(const AttnArgs a) {
       body(t + 1, Odd{}, std::false_type{});
     }
     for (; t < n_tiles; ++t) body(t, Any{}, std::true_type{});   // masking a fully visible tile is harmless
+    wait_loads();
     __syncthreads();               // V of the last tile has landed for everybody
     {
       // O += P_Y V of the last tile
@@ -521,6 +554,7 @@ attention_kernel(const AttnArgs a) {
       __syncthreads();                                   // the tile buffer is free
       issue_any(kc, kn, lds_k, t, ld_chunk_k);
       issue_any(vc, vn, lds_v, t, ld_chunk_v);
+      wait_loads();
       __syncthreads();                                   // and full again
       if (!active) continue;
       for (int blk = 0; blk < S::kTk / 32; ++blk) {
@@ -601,17 +635,23 @@ hipError_t launch_shape(const AttnArgs& a, hipStream_t s) {
     attr_done = true;
   }
   const int grid = kXcds * a.work_per_xcd;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), S::kLdsBytes, s, a);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(S::kThreads), S::kLdsBytes, s, a);
   return hipGetLastError();
 }
 
-constexpr int kRowsOfVariant[2] = {128, 64};
+constexpr int kRowsOfVariant[3] = {128, 64, 128};
 
 }  // namespace
 
 void plan_attention(AttnArgs& a, int /*head_dim*/) {
   auto wgs = [&](int rows) { return ((a.n + rows - 1) / rows) * a.n_q_heads; };
-  a.variant = wgs(128) >= 192 ? 0 : 1;
+  // eight waves x 32 rows (two waves per SIMD) when 128-row workgroups fill the chip,
+  // otherwise four waves x 32 rows over 64-row workgroups
+  a.variant = wgs(128) >= 192 ? 2 : 1;
+  if (const char* e = getenv("KVP_ATTN_VARIANT")) {                      // tuning aid: 0, 1 or 2
+    const int v = atoi(e);
+    if (v >= 0 && v <= 2) a.variant = v;
+  }
   const int rows = kRowsOfVariant[a.variant];
   a.n_row_tiles = (a.n + rows - 1) / rows;
   a.total_work = a.n_row_tiles * a.n_q_heads;
@@ -621,9 +661,11 @@ void plan_attention(AttnArgs& a, int /*head_dim*/) {
 hipError_t launch_attention(const AttnArgs& a, int head_dim, hipStream_t s) {
   if (head_dim == 128) {
     if (a.variant == 0) return launch_shape<128, 2, 2, 2>(a, s);
+    if (a.variant == 2) return launch_shape<128, 1, 4, 2>(a, s);
     return launch_shape<128, 1, 2, 2>(a, s);
   }
   if (a.variant == 0) return launch_shape<64, 2, 2, 2>(a, s);
+  if (a.variant == 2) return launch_shape<64, 1, 4, 2>(a, s);
   return launch_shape<64, 1, 2, 2>(a, s);
 }
 

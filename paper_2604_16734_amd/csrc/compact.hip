@@ -80,26 +80,43 @@ merge_kernel(const CompactArgs a) {
   };
   auto weight_of = [&](int pos) -> float { return pos < a.c ? wts[pos] : 1.f; };
 
-  const float wd = weight_of(e.pos);
-  float total = wd;
-  float acc[2 * W];
-  {
-    const Row<W> r = load_row<W>(row_of(e.pos), l32);
+  // fetch the destination and all (at most six) sources at once, then add them up in order
+  // sources arrive in no particular order: sort them by candidate position (unused slots last)
+  // so that the fp32 sum below is taken in one fixed order
+  int pos[kNeighbours + 1];
+  pos[0] = e.pos;
 #pragma unroll
-    for (int k = 0; k < W; ++k) {
-      acc[2 * k] = wd * bf16_lo(r.w[k]);
-      acc[2 * k + 1] = wd * bf16_hi(r.w[k]);
+  for (int k = 0; k < kNeighbours; ++k) pos[k + 1] = k < e.n_src ? e.src[k] : 0x7FFFFFFF;
+#pragma unroll
+  for (int pass = 0; pass < kNeighbours; ++pass)
+#pragma unroll
+    for (int k = 1 + (pass & 1); k + 1 <= kNeighbours; k += 2) {
+      const int lo = min(pos[k], pos[k + 1]), hi = max(pos[k], pos[k + 1]);
+      pos[k] = lo; pos[k + 1] = hi;
     }
+  float wt[kNeighbours + 1];
+  Row<W> rows[kNeighbours + 1];
+#pragma unroll
+  for (int k = 0; k <= kNeighbours; ++k) {
+    const bool on = k <= e.n_src;
+    const int pk = on ? pos[k] : e.pos;          // an unused entry re-reads the destination, weight 0
+    wt[k] = on ? weight_of(pk) : 0.f;
+    rows[k] = load_row<W>(row_of(pk), l32);
   }
-  for (int s = 0; s < e.n_src; ++s) {
-    const int sp = e.src[s];
-    const float ws = weight_of(sp);
-    const Row<W> r = load_row<W>(row_of(sp), l32);
-    total += ws;
+  float total = wt[0];
+  float acc[2 * W];
+#pragma unroll
+  for (int k = 0; k < W; ++k) {
+    acc[2 * k] = wt[0] * bf16_lo(rows[0].w[k]);
+    acc[2 * k + 1] = wt[0] * bf16_hi(rows[0].w[k]);
+  }
+#pragma unroll
+  for (int s = 1; s <= kNeighbours; ++s) {
+    total += wt[s];
 #pragma unroll
     for (int k = 0; k < W; ++k) {
-      acc[2 * k] = __builtin_fmaf(ws, bf16_lo(r.w[k]), acc[2 * k]);
-      acc[2 * k + 1] = __builtin_fmaf(ws, bf16_hi(r.w[k]), acc[2 * k + 1]);
+      acc[2 * k] = __builtin_fmaf(wt[s], bf16_lo(rows[s].w[k]), acc[2 * k]);
+      acc[2 * k + 1] = __builtin_fmaf(wt[s], bf16_hi(rows[s].w[k]), acc[2 * k + 1]);
     }
   }
   Row<W> res;

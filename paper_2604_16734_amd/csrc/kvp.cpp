@@ -283,7 +283,7 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
       return KVP_EINVAL;
     }
     t += s.n_tokens;
-    if (t > 0x7FFFFFFF) return KVP_EINVAL;
+    if (t > (1 << 24)) return KVP_EINVAL;   // the select kernel splits token indices with fp32 reciprocals
   }
   const Layout lay = make_layout(*cfg);
   if (!dry && device_bytes < lay.total_bytes) return KVP_ENOMEM;

@@ -28,8 +28,8 @@ struct AttnArgs {
   float scale_log2;    // softmax scale times log2(e)
 };
 
-// Column sums of the softmax matrix (Eq. 4 summed over rows), one partial
-// array per (query head of the group, row split).
+// Column sums of the softmax matrix (Eq. 4 summed over rows and over the query
+// heads of a KV group), one partial array per row split.
 struct ColsumArgs {
   const u16* q;
   const u16* k_new;
@@ -38,6 +38,7 @@ struct ColsumArgs {
   float* partial;      // [Hkv, n_partials, cand_stride]
   int n, c, n_q_heads, n_kv_heads, budget, lse_stride, cand_stride;
   int n_kv_blocks, row_splits, q_tiles_per_split, n_partials;
+  int subtiles;        // 32-key subtiles per wave, chosen by plan_colsum
   int work_per_xcd, total_work;
   float scale_log2;
 };

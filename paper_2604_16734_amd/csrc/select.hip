@@ -14,8 +14,11 @@
 //     the k-th kept block token (ascending token index) gets the k-th free slot.
 //   * merge plan: a token -> position hash table over the cached tokens (block
 //     tokens map directly); every evicted visual candidate looks at its grid
-//     neighbours and takes the kept one with the largest key; every kept
-//     candidate then collects the sources that chose it.
+//     neighbours, takes the kept one with the largest key and counts itself in
+//     at that destination; a prefix sum numbers the destinations that were
+//     chosen, and the sources then write themselves into their destination's
+//     entry (the merge kernel sorts each entry, so the order they arrive in
+//     does not matter).
 #include "kvp_internal.h"
 
 namespace kvp {
@@ -48,7 +51,8 @@ struct Lds {
   int* tok;           // [cand_pad]
   unsigned short* free_list;  // [cand_pad]
   unsigned short* dst;        // [cand_pad]
-  unsigned char* keep;        // [cand_pad]
+  unsigned char* keep;        // [cand_pad]; reused as per-destination fill counters
+  unsigned* cnt;              // [cand_pad / 4] one byte per candidate: sources that chose it
   unsigned* shared;   // histogram (256 x 32 u32) or hash table (table_size u16), whichever is larger
 };
 
@@ -80,28 +84,43 @@ __device__ __forceinline__ int find_pos(const Lds& l, unsigned mask, int tok, in
   }
 }
 
-// grid neighbours of a visual token: left, right, up, down, previous plane, next plane
-__device__ __forceinline__ int neighbours(const Seg* segs, int n_segs, int tok, int* out) {
+struct SegL {          // a prefix segment in LDS, with reciprocals for the coordinate split
+  int begin, n, kind, gh, gw, planes, temporal, per;
+  float inv_per, inv_gw;
+};
+
+// u / d and u % d for 0 <= u < 2^24, d >= 1, with a float reciprocal and one fix-up step
+__device__ __forceinline__ void div_mod(int u, int d, float inv_d, int& q, int& r) {
+  q = (int)((float)u * inv_d);
+  r = u - q * d;
+  if (r < 0) { r += d; --q; }
+  if (r >= d) { r -= d; ++q; }
+}
+
+// grid neighbours of a visual token: left, right, up, down, previous plane, next plane;
+// out[j] = -1 where there is none.  Returns false for a text token.
+__device__ __forceinline__ bool neighbours(const SegL* segs, int n_segs, int tok, int (&out)[kNeighbours]) {
+#pragma unroll
+  for (int j = 0; j < kNeighbours; ++j) out[j] = -1;
   for (int s = 0; s < n_segs; ++s) {
-    const Seg sg = segs[s];
-    if (tok < sg.begin || tok >= sg.begin + sg.n) continue;
-    if (sg.kind != KVP_VISUAL) return -1;
-    const int u = tok - sg.begin;
-    const int per = sg.gh * sg.gw;
-    const int plane = u / per, rem = u % per;
-    const int y = rem / sg.gw, x = rem % sg.gw;
-    int k = 0;
-    if (x > 0) out[k++] = tok - 1;
-    if (x + 1 < sg.gw) out[k++] = tok + 1;
-    if (y > 0) out[k++] = tok - sg.gw;
-    if (y + 1 < sg.gh) out[k++] = tok + sg.gw;
+    const int begin = segs[s].begin;
+    if (tok < begin || tok >= begin + segs[s].n) continue;
+    const SegL sg = segs[s];
+    if (sg.kind != KVP_VISUAL) return false;
+    int plane, rem, y, x;
+    div_mod(tok - sg.begin, sg.per, sg.inv_per, plane, rem);
+    div_mod(rem, sg.gw, sg.inv_gw, y, x);
+    if (x > 0) out[0] = tok - 1;
+    if (x + 1 < sg.gw) out[1] = tok + 1;
+    if (y > 0) out[2] = tok - sg.gw;
+    if (y + 1 < sg.gh) out[3] = tok + sg.gw;
     if (sg.temporal) {
-      if (plane > 0) out[k++] = tok - per;
-      if (plane + 1 < sg.planes) out[k++] = tok + per;
+      if (plane > 0) out[4] = tok - sg.per;
+      if (plane + 1 < sg.planes) out[5] = tok + sg.per;
     }
-    return k;
+    return true;
   }
-  return -1;
+  return false;
 }
 
 __global__ void __launch_bounds__(kThreads)
@@ -111,7 +130,7 @@ select_kernel(const SelectArgs a) {
   __shared__ unsigned s_digit, s_want, s_bin_count, s_n_dst;
   __shared__ unsigned s_bin[256];
   __shared__ unsigned s_wave_tot[kWaves];
-  __shared__ Seg s_segs[KVP_MAX_SEGMENTS];
+  __shared__ SegL s_segs[KVP_MAX_SEGMENTS];
 
   const int hk = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -127,25 +146,68 @@ select_kernel(const SelectArgs a) {
     l.free_list = reinterpret_cast<unsigned short*>(p); p += (size_t)cand_pad * 2;
     l.dst = reinterpret_cast<unsigned short*>(p); p += (size_t)cand_pad * 2;
     l.keep = p; p += (size_t)cand_pad;
+    l.cnt = reinterpret_cast<unsigned*>(p); p += (size_t)cand_pad;
     l.shared = reinterpret_cast<unsigned*>(p);
   }
 
   // ---- scores (sum of the partial column sums in a fixed order) and token indices
+  // Thread t takes candidates t, t + 1024, ...; the partial sums of all of them are fetched
+  // together, eight partials per round, so that many loads are in flight at once.
   float* scores = a.scores + (size_t)hk * a.cand_stride;
-  for (int p = tid; p < n_cand; p += kThreads) {
-    float sc;
+  {
+    float acc[kMaxItems];
+#pragma unroll
+    for (int i = 0; i < kMaxItems; ++i) acc[i] = 0.f;
     if (a.score_override) {
-      sc = a.score_override[(size_t)hk * n_cand + p];
+#pragma unroll
+      for (int i = 0; i < kMaxItems; ++i) {
+        const int p = tid + i * kThreads;
+        if (p < n_cand) acc[i] = a.score_override[(size_t)hk * n_cand + p];
+      }
     } else {
-      sc = 0.f;
-      const float* part = a.partial + (size_t)hk * a.n_partials * a.cand_stride + p;
-      for (int j = 0; j < a.n_partials; ++j) sc += part[(size_t)j * a.cand_stride];
+      const float* part = a.partial + (size_t)hk * a.n_partials * a.cand_stride;
+      int j = 0;
+      for (; j + 8 <= a.n_partials; j += 8) {
+        float v[8][kMaxItems];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int i = 0; i < kMaxItems; ++i) {
+            const int p = tid + i * kThreads;
+            v[u][i] = (i < items && p < n_cand) ? part[(size_t)(j + u) * a.cand_stride + p] : 0.f;
+          }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int i = 0; i < kMaxItems; ++i) acc[i] += v[u][i];
+      }
+      for (; j < a.n_partials; ++j)
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i) {
+          const int p = tid + i * kThreads;
+          if (p < n_cand) acc[i] += part[(size_t)j * a.cand_stride + p];
+        }
     }
-    scores[p] = sc;
-    l.sc[p] = order_bits(sc);
-    l.tok[p] = p < c ? a.token_idx[(size_t)hk * budget + p] : a.t0 + (p - c);
+#pragma unroll
+    for (int i = 0; i < kMaxItems; ++i) {
+      const int p = tid + i * kThreads;
+      if (p < n_cand) {
+        scores[p] = acc[i];
+        l.sc[p] = order_bits(acc[i]);
+        l.tok[p] = p < c ? a.token_idx[(size_t)hk * budget + p] : a.t0 + (p - c);
+      }
+    }
   }
-  if (tid < a.n_segs) s_segs[tid] = a.segs[tid];
+  if (tid < a.n_segs) {
+    const Seg g = a.segs[tid];
+    SegL sl;
+    sl.begin = g.begin; sl.n = g.n; sl.kind = g.kind; sl.gh = g.gh; sl.gw = g.gw;
+    sl.planes = g.planes; sl.temporal = g.temporal;
+    sl.per = g.gh * g.gw;
+    sl.inv_per = sl.per > 0 ? 1.f / (float)sl.per : 0.f;
+    sl.inv_gw = g.gw > 0 ? 1.f / (float)g.gw : 0.f;
+    s_segs[tid] = sl;
+  }
   if (tid == 0) s_n_dst = 0;
   __syncthreads();
 
@@ -288,6 +350,7 @@ select_kernel(const SelectArgs a) {
   // ---- merge plan
   const unsigned mask = (unsigned)a.table_size - 1u;
   for (int i = tid; i < a.table_size / 2; i += kThreads) l.shared[i] = 0xFFFFFFFFu;
+  for (int i = tid; i < cand_pad / 4; i += kThreads) l.cnt[i] = 0u;
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < kMaxItems; ++i) {
@@ -295,52 +358,82 @@ select_kernel(const SelectArgs a) {
     if (valid[i] && p < c) table_insert(l.shared, mask, l.tok[p], (unsigned)p);
   }
   __syncthreads();
-  // every evicted visual candidate picks its best kept neighbour
+  // every evicted visual candidate picks its best kept neighbour and counts itself in there
 #pragma unroll
   for (int i = 0; i < kMaxItems; ++i) {
     if (!valid[i] || keep[i]) continue;
     const int p = tid * items + i;
     int nb[kNeighbours];
-    const int k = neighbours(s_segs, a.n_segs, l.tok[p], nb);
+    if (!neighbours(s_segs, a.n_segs, l.tok[p], nb)) continue;
+    int r[kNeighbours];
+#pragma unroll
+    for (int j = 0; j < kNeighbours; ++j) r[j] = nb[j] >= 0 ? find_pos(l, mask, nb[j], c, n, a.t0) : -1;
     unsigned long long best_key = 0;
     int best = -1;
-    for (int j = 0; j < k; ++j) {
-      const int r = find_pos(l, mask, nb[j], c, n, a.t0);
-      if (r < 0 || !l.keep[r]) continue;
-      const unsigned long long kr = make_key(l.sc[r], l.tok[r]);
-      if (best < 0 || kr > best_key) { best = r; best_key = kr; }
+#pragma unroll
+    for (int j = 0; j < kNeighbours; ++j) {
+      if (r[j] < 0 || !l.keep[r[j]]) continue;
+      const unsigned long long kr = make_key(l.sc[r[j]], l.tok[r[j]]);
+      if (best < 0 || kr > best_key) { best = r[j]; best_key = kr; }
     }
     if (best >= 0) {
       l.dst[p] = (unsigned short)best;
       a.dst[(size_t)hk * a.cand_stride + p] = best;
+      atomicAdd(&l.cnt[best >> 2], 1u << (8 * (best & 3)));
     }
   }
   __syncthreads();
-  // every kept visual candidate collects the sources that chose it
+  // number the destinations that were chosen, in candidate order
+  unsigned short* jmap = l.free_list;                       // the free list has been consumed
+  unsigned* fill = reinterpret_cast<unsigned*>(l.keep);     // so have the keep flags
+  unsigned n_mine = 0;
+  unsigned cnt_of[kMaxItems];
+#pragma unroll
+  for (int i = 0; i < kMaxItems; ++i) {
+    const int p = tid * items + i;
+    cnt_of[i] = valid[i] ? (l.cnt[p >> 2] >> (8 * (p & 3))) & 0xFFu : 0u;
+    n_mine += cnt_of[i] ? 1u : 0u;
+  }
+  unsigned incl2 = n_mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned v = __shfl_up(incl2, off, 64);
+    if (lane >= off) incl2 += v;
+  }
+  __syncthreads();                       // everybody has read keep[] and cnt[]; s_wave_tot is free
+  if (lane == 63) s_wave_tot[wave] = incl2;
+  for (int i = tid; i < cand_pad / 4; i += kThreads) fill[i] = 0u;
+  __syncthreads();
+  unsigned ord = incl2 - n_mine, n_dst = 0;
+  for (int w2 = 0; w2 < kWaves; ++w2) {
+    const unsigned t = s_wave_tot[w2];
+    if (w2 < wave) ord += t;
+    n_dst += t;
+  }
   DstEntry* dsts = a.dsts + (size_t)hk * a.chunk_max;
 #pragma unroll
   for (int i = 0; i < kMaxItems; ++i) {
-    if (!valid[i] || !keep[i]) continue;
+    if (!cnt_of[i]) continue;
     const int p = tid * items + i;
-    int nb[kNeighbours];
-    const int k = neighbours(s_segs, a.n_segs, l.tok[p], nb);
-    DstEntry e;
-    e.pos = p;
-    e.n_src = 0;
-#pragma unroll
-    for (int j = 0; j < kNeighbours; ++j) e.src[j] = -1;
-    for (int j = 0; j < k; ++j) {
-      const int r = find_pos(l, mask, nb[j], c, n, a.t0);
-      if (r >= 0 && !l.keep[r] && l.dst[r] == (unsigned short)p) e.src[e.n_src++] = r;
-    }
-    if (e.n_src > 0) {
-      const unsigned j = atomicAdd(&s_n_dst, 1u);
-      dsts[j] = e;
-      if (rank_new[i] >= 0) moves[rank_new[i]].stage = (int)j;
-    }
+    jmap[p] = (unsigned short)ord;
+    dsts[ord].pos = p;
+    dsts[ord].n_src = (int)cnt_of[i];
+    if (rank_new[i] >= 0) moves[rank_new[i]].stage = (int)ord;
+    ++ord;
   }
   __syncthreads();
-  if (tid == 0) a.counts[hk].n_dst = (int)s_n_dst;
+  // every source writes itself into its destination's entry
+#pragma unroll
+  for (int i = 0; i < kMaxItems; ++i) {
+    if (!valid[i] || keep[i]) continue;
+    const int p = tid * items + i;
+    const unsigned d = l.dst[p];
+    if (d == kNone16) continue;
+    const unsigned old = atomicAdd(&fill[d >> 2], 1u << (8 * (d & 3)));
+    const unsigned k = (old >> (8 * (d & 3))) & 0xFFu;
+    dsts[jmap[d]].src[k] = p;
+  }
+  if (tid == 0) a.counts[hk].n_dst = (int)n_dst;
 }
 
 }  // namespace
@@ -350,7 +443,7 @@ size_t select_lds_bytes(int /*n_cand*/, int items, int table_size) {
   size_t shared = (size_t)256 * kCopies * 4;
   const size_t table = (size_t)table_size * 2;
   if (table > shared) shared = table;
-  return cand_pad * (4 + 4 + 2 + 2 + 1) + shared;
+  return cand_pad * (4 + 4 + 2 + 2 + 1 + 1) + shared;
 }
 
 hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s) {
