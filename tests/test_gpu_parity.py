@@ -98,6 +98,33 @@ def test_scores_and_free_selection(hq, hkv, d, c, n, budget, chunk_max, scale):
     cache.close()
 
 
+@pytest.mark.parametrize("hq,hkv,d,c,n", [(4, 2, 64, 100, 150), (8, 2, 128, 256, 300), (4, 4, 128, 0, 96)])
+def test_runaway_logits_take_the_careful_path(hq, hkv, d, c, n):
+    """Logits that climb by hundreds of nats along the keys: the fixed softmax reference of the
+    fast loop would overflow, so the kernel must detect it and redo the rows exactly."""
+    from kvp_workload import f32_to_bf16_bits
+    rng = np.random.default_rng(d + c)
+    budget, chunk_max = 4096, 512
+    segs = [Segment(0, 100000, 0)]
+    cache = K.Cache(1, hq, hkv, d, budget, chunk_max, segs, merge=False, device=DEV)
+    tot = c + n
+    ramp = (np.arange(tot, dtype=np.float32) / tot)[:, None, None]                   # later keys score higher
+    k_all = (8.0 * ramp * np.ones((tot, hkv, d), dtype=np.float32)) + 0.05 * rng.standard_normal((tot, hkv, d)).astype(np.float32)
+    v_all = rng.standard_normal((tot, hkv, d)).astype(np.float32)
+    q = (8.0 * np.ones((n, hq, d), dtype=np.float32)) + 0.05 * rng.standard_normal((n, hq, d)).astype(np.float32)
+    kb, vb, qb = f32_to_bf16_bits(k_all), f32_to_bf16_bits(v_all), f32_to_bf16_bits(q)
+    oc = O.LayerCache(hkv, d, budget)
+    if c:
+        oc.compact(0, O.bf16_bits_to_f64(kb[:c]), O.bf16_bits_to_f64(vb[:c]), np.zeros((hkv, c), dtype=np.float32))
+    U.upload_state(cache, 0, oc)
+    cache.set_state(0, c, c)
+    out = cache.prefill_chunk(0, c, U.bits_to_torch(qb), U.bits_to_torch(kb[c:]), U.bits_to_torch(vb[c:]))
+    out_ref, scores_ref = oc.attend(c, O.bf16_bits_to_f64(qb), O.bf16_bits_to_f64(kb[c:]), O.bf16_bits_to_f64(vb[c:]))
+    assert np.isfinite(U.torch_bf16_to_f64(out)).all()
+    assert U.out_rel_err(U.torch_bf16_to_f64(out), out_ref) <= U.OUT_TOL
+    cache.close()
+
+
 def test_select_ties_and_override():
     """All scores equal: the lowest token indices stay (ties to the lower index)."""
     hq = hkv = 2
