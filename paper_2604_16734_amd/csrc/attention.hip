@@ -241,6 +241,12 @@ attention_kernel(const AttnArgs a) {
       for (int s = 0; s < D / 16; ++s)
         qf[t][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + 16 * s));
     }
+    // Make the compiler finish these loads here.  Left pending, it would wait for them inside the
+    // loop, at a point where the hand-issued tile loads are in flight, and drain those as well.
+#pragma unroll
+    for (int t = 0; t < QT; ++t)
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(qf[t][s]));
     f32x16 o[QT][D / 32];
     float m_ref[QT], l_run[QT];
 #pragma unroll

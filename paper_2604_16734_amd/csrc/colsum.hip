@@ -34,8 +34,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kRing = 4;               // LDS query-tile buffers
 constexpr int kAhead = 3;              // tiles in flight ahead of the one in use
-constexpr int kMaxRowSplits = 8;
-constexpr int kTargetWorkgroups = 512;
+constexpr int kMaxRowSplits = 16;
+constexpr int kTargetWorkgroups = 768;    // three per CU: two resident, startup of the third hidden
 
 // NT = 32-key subtiles per wave: a wave owns 32 NT keys, a workgroup 128 NT
 template <int D, int NT>
@@ -75,6 +75,12 @@ colsum_kernel(const ColsumArgs a) {
     for (int s = 0; s < D / 16; ++s)
       kf[t][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + 16 * s + 8 * g));
   }
+  // Make the compiler finish these loads here.  Left pending, it would wait for them inside the
+  // loop, at a point where the hand-issued tile loads are in flight, and drain those as well.
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(kf[t][s]));
 
   // rows [qt_begin, qt_end) in units of 32-row tiles; rows before the block's first key see none
   // of its block keys, so a block past the cache starts later
@@ -133,8 +139,10 @@ colsum_kernel(const ColsumArgs a) {
     for (int i = 0; i < kAhead; ++i) issue_step(i);
     for (int i = 0; i < n_steps; ++i) {
       // tile i has landed for this wave when at most the loads of the (kAhead - 1) later tiles remain
-      __builtin_amdgcn_s_waitcnt(0x0F70 | ((kAhead - 1) * kLoadsPerStep));
-      __syncthreads();                 // ... and for everybody; everybody is also done with tile i - 1
+      // ... and for everybody after the barrier; everybody is also done with tile i - 1 then.
+      // A bare s_barrier on purpose: __syncthreads() carries a fence that drains ALL loads in
+      // flight, which would throw the prefetch ring away at every step.
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((kAhead - 1) * kLoadsPerStep) : "memory");
       issue_step(i + kAhead);          // into the buffer of tile i - 1
       const int buf = i % kRing;
       const int row0 = (qt_begin + i % tiles) * 32;
@@ -180,7 +188,7 @@ colsum_kernel(const ColsumArgs a) {
         }
       }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // the surplus loads must not outlive the workgroup's LDS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the surplus loads must not outlive the workgroup's LDS
   }
 
   // lanes l and l + 32 hold the two halves of the rows of one key column
