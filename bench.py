@@ -174,6 +174,8 @@ def main():
     ap.add_argument("--workload", default="long_video")
     ap.add_argument("--others", type=int, default=1, help="also time the other four shapes (few steps)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (no collectives, "
@@ -188,6 +190,13 @@ def main():
     device = "cuda:0"
     threads = min(16, len(os.sched_getaffinity(0)))
     wl = get_workload(args.workload)
+    if args.copy_probe:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=device).fill_(1)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     main_res = bench_workload(wl, args.steps, args.warmup, device, threads)
 
     others = {}

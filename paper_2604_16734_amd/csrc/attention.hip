@@ -112,7 +112,9 @@ struct Shape {
   static constexpr int kTileBytes = 4 * kTile * 2;    // two K and two V buffers
   static constexpr int kMergeFloats = QT * (D / 32) * 16 * 64 + 2 * QT * 64;  // per wave
   static constexpr int kMergeBytes = (KS - 1) * QW * kMergeFloats * 4;
-  static constexpr int kLdsBytes = kTileBytes > kMergeBytes ? kTileBytes : kMergeBytes;
+  static constexpr int kStripRow = 2 * D + 16;        // bytes of an output row staged in LDS, padded
+  static constexpr int kEpilogueBytes = kMergeBytes + QW * 32 * kStripRow;
+  static constexpr int kLdsBytes = kTileBytes > kEpilogueBytes ? kTileBytes : kEpilogueBytes;
   static_assert(kWaves == 4 || kWaves == 8, "four or eight waves per workgroup");
   static_assert(kTk == 128, "the staging map assumes 128-key tiles");
 };
@@ -510,25 +512,34 @@ attention_kernel(const AttnArgs a) {
           }
         }
       }
-      // ---- normalise and store; lane holds O[row][32 dt + 8 j + 4 g + 0..3]
+      // ---- normalise and store; lane holds O[row][32 dt + 8 j + 4 g + 0..3].  The rows go
+      // through a private LDS strip of the wave so that the global stores are whole 16-byte
+      // chunks of consecutive addresses (a row of the output is 2 D contiguous bytes).
       if (ks == 0) {
+        unsigned char* strip = lds_raw + S::kMergeBytes + (size_t)qw * 32 * S::kStripRow;
 #pragma unroll
         for (int tq = 0; tq < QT; ++tq) {
           const int row = q0 + 32 * tq + l32;
-          if (row < n) {
-            const float inv = 1.f / l_run[tq];
-            u16* dstp = a.out + ((size_t)row * a.n_q_heads + h) * D + 4 * g;
+          const float inv = 1.f / l_run[tq];
 #pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt)
+          for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                u32x2 pk;
-                pk.x = pack_bf16(o[tq][dt][4 * j] * inv, o[tq][dt][4 * j + 1] * inv);
-                pk.y = pack_bf16(o[tq][dt][4 * j + 2] * inv, o[tq][dt][4 * j + 3] * inv);
-                *reinterpret_cast<u32x2*>(dstp + 32 * dt + 8 * j) = pk;
-              }
-            if (g == 0)
-              a.lse2[(size_t)h * a.lse_stride + row] = m_ref[tq] * sl2 + __builtin_log2f(l_run[tq]);
+            for (int j = 0; j < 4; ++j) {
+              u32x2 pk;
+              pk.x = pack_bf16(o[tq][dt][4 * j] * inv, o[tq][dt][4 * j + 1] * inv);
+              pk.y = pack_bf16(o[tq][dt][4 * j + 2] * inv, o[tq][dt][4 * j + 3] * inv);
+              *reinterpret_cast<u32x2*>(strip + l32 * S::kStripRow + 2 * (32 * dt + 8 * j + 4 * g)) = pk;
+            }
+          if (g == 0 && row < n)
+            a.lse2[(size_t)h * a.lse_stride + row] = m_ref[tq] * sl2 + __builtin_log2f(l_run[tq]);
+#pragma unroll
+          for (int it = 0; it < D / 16; ++it) {
+            const int idx = it * 64 + lane;
+            const int r = idx / (D / 8), ch = idx % (D / 8);
+            const u32x4 val = *reinterpret_cast<const u32x4*>(strip + r * S::kStripRow + 16 * ch);
+            const int orow = q0 + 32 * tq + r;
+            if (orow < n)
+              *reinterpret_cast<u32x4*>(a.out + ((size_t)orow * a.n_q_heads + h) * D + 8 * ch) = val;
           }
         }
       }

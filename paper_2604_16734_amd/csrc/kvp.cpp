@@ -453,10 +453,10 @@ int kvp_profile_read(kvp_cache* c, kvp_kernel_stat* stats) {
 void kvp_free_cache(kvp_cache* c) {
   if (!c) return;
   for (ProfEvent& pe : c->events) {
-    hipEventDestroy(pe.start);
-    hipEventDestroy(pe.stop);
+    (void)hipEventDestroy(pe.start);
+    (void)hipEventDestroy(pe.stop);
   }
-  for (hipEvent_t e : c->pool) hipEventDestroy(e);
+  for (hipEvent_t e : c->pool) (void)hipEventDestroy(e);
   delete c;
 }
 
