@@ -19,7 +19,10 @@
  *  - Every function returns KVP_OK (0) or a negative code.  Nothing throws,
  *    exits, synchronises a stream or allocates device memory: all device
  *    memory is the single buffer the caller passes to kvp_init_cache.
- *  - On any error no device work has been enqueued and no state has changed.
+ *  - On KVP_EINVAL, KVP_ESTATE and KVP_ENOMEM no device work has been enqueued
+ *    and no state has changed.  KVP_EDEVICE is the exception: the HIP runtime
+ *    refused a launch part-way, earlier kernels of the same call may already
+ *    be enqueued, and the layer must be treated as lost (free the cache).
  *  - Pointers named q, k, v, out, scores_override and device_buf are DEVICE
  *    pointers; cfg, segs and all out-parameters are HOST pointers.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -28,6 +31,10 @@
  *    and token ranges are consecutive from 0.  A layer is PENDING between
  *    its prefill_chunk and its compact, READY otherwise.
  *  - A kvp_cache is not thread-safe; use one host thread per cache.
+ *  - Tuning aid: the environment variable KVP_ATTN_VARIANT (0, 1 or 2), read at
+ *    every kvp_prefill_chunk, forces one of the attention kernel's workgroup
+ *    shapes instead of the one chosen from the launch size.  Results are the
+ *    same to rounding; only speed differs.
  */
 #ifndef KVP_H
 #define KVP_H

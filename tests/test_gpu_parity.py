@@ -67,6 +67,17 @@ def test_attention_and_scores(hq, hkv, d, c, n, budget, chunk_max):
     cache.close()
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("hq,hkv,d,c,n", [(8, 2, 128, 193, 300), (4, 4, 64, 70, 200), (4, 2, 128, 0, 129)])
+def test_every_workgroup_shape(monkeypatch, variant, hq, hkv, d, c, n):
+    # the library picks the attention workgroup shape from the launch size; the tuning
+    # variable forces each compiled shape in turn so that none goes untested
+    monkeypatch.setenv("KVP_ATTN_VARIANT", str(variant))
+    cache, oc, err, scores_ref, _ = _attention_case(hq, hkv, d, c, n, 4096, 512, seed=7 * c + n + variant)
+    assert err <= U.OUT_TOL, err
+    cache.close()
+
+
 @pytest.mark.parametrize("hq,hkv,d,c,n,budget,chunk_max,scale", [
     (4, 4, 64, 128, 64, 128, 64, 0.0),
     (8, 2, 128, 200, 150, 200, 256, 0.0),
