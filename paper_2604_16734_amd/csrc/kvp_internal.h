@@ -30,6 +30,7 @@ struct AttnArgs {
 
 // Column sums of the softmax matrix (Eq. 4 summed over rows and over the query
 // heads of a KV group), one partial array per row split.
+constexpr int kColsumMaxKvBlocks = 64;
 struct ColsumArgs {
   const u16* q;
   const u16* k_new;
@@ -37,10 +38,15 @@ struct ColsumArgs {
   const float* lse2;
   float* partial;      // [Hkv, n_partials, cand_stride]
   int n, c, n_q_heads, n_kv_heads, budget, lse_stride, cand_stride;
-  int n_kv_blocks, row_splits, q_tiles_per_split, n_partials;
+  int n_kv_blocks;     // blocks of 256 * subtiles keys
+  int n_partials;      // the most row splits any key block has; every key gets that many partials
   int subtiles;        // 32-key subtiles per wave, chosen by plan_colsum
+  int wgs_per_head;    // = split_prefix[n_kv_blocks]
   int work_per_xcd, total_work;
   float scale_log2;
+  // workgroups [split_prefix[k], split_prefix[k + 1]) of a head share key block k and split the
+  // 32-row query tiles that see it evenly among themselves
+  int split_prefix[kColsumMaxKvBlocks + 1];
 };
 
 // Device copy of one prefix segment.
