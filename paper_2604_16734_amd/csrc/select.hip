@@ -46,14 +46,22 @@ __device__ __forceinline__ unsigned hash_tok(int tok, unsigned mask) {
   return x & mask;
 }
 
+// bytes of the region that is first the radix histogram and then the compaction lists
+__host__ __device__ inline size_t select_region_bytes(size_t cand_pad) {
+  const size_t hist = (size_t)256 * kCopies * 4, lists = cand_pad * 5;
+  return (hist > lists ? hist : lists + 15) / 16 * 16;
+}
+
 struct Lds {
-  unsigned* sc;       // [cand_pad] order-preserving score bits
+  unsigned* sc;       // [cand_pad] order-preserving score bits; later the ordinal of a merge destination
   int* tok;           // [cand_pad]
-  unsigned short* free_list;  // [cand_pad]
-  unsigned short* dst;        // [cand_pad]
   unsigned char* keep;        // [cand_pad]; reused as per-destination fill counters
+  // one region, two lives: the radix histogram (256 x kCopies u32), then the compaction lists
+  unsigned* hist;
+  unsigned short* evicted;    // [cand_pad] positions of the evicted candidates, ascending
+  unsigned short* free_dst;   // [cand_pad] free slots by rank; then the destination of the e-th evicted
   unsigned* cnt;              // [cand_pad / 4] one byte per candidate: sources that chose it
-  unsigned* shared;   // histogram (256 x 32 u32) or hash table (table_size u16), whichever is larger
+  unsigned* table;    // token -> position of the cached tokens: table_size u16, open addressing
 };
 
 __device__ __forceinline__ void table_insert(unsigned* words, unsigned mask, int tok, unsigned pos) {
@@ -72,15 +80,17 @@ __device__ __forceinline__ void table_insert(unsigned* words, unsigned mask, int
   }
 }
 
-// position of token `tok` among the candidates, or -1
-__device__ __forceinline__ int find_pos(const Lds& l, unsigned mask, int tok, int c, int n, int t0) {
-  if (tok >= t0 && tok < t0 + n) return c + (tok - t0);
-  unsigned h = hash_tok(tok, mask);
+__device__ __forceinline__ unsigned table_entry(const Lds& l, unsigned h) {
+  return (l.table[h >> 1] >> ((h & 1u) * 16u)) & 0xFFFFu;
+}
+
+// position of cached token `tok`, or -1, when its home slot `h` holds `e` and that is not it
+__device__ __forceinline__ int probe_on(const Lds& l, unsigned mask, int tok, unsigned h, unsigned e) {
   for (;;) {
-    const unsigned e = (l.shared[h >> 1] >> ((h & 1u) * 16u)) & 0xFFFFu;
     if (e == kNone16) return -1;
     if (l.tok[e] == tok) return (int)e;
     h = (h + 1) & mask;
+    e = table_entry(l, h);
   }
 }
 
@@ -127,9 +137,9 @@ __global__ void __launch_bounds__(kThreads)
 select_kernel(const SelectArgs a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   __shared__ unsigned long long s_threshold;
-  __shared__ unsigned s_digit, s_want, s_bin_count, s_n_dst;
+  __shared__ unsigned s_digit, s_want, s_bin_count;
   __shared__ unsigned s_bin[256];
-  __shared__ unsigned s_wave_tot[kWaves];
+  __shared__ unsigned s_wave_tot[kWaves], s_wave_ev[kWaves];
   __shared__ SegL s_segs[KVP_MAX_SEGMENTS];
 
   const int hk = blockIdx.x;
@@ -137,78 +147,98 @@ select_kernel(const SelectArgs a) {
   const int c = a.c, n = a.n, n_cand = c + n, budget = a.budget;
   const int items = a.items;
   const int cand_pad = items * kThreads;
+  const unsigned mask = (unsigned)a.table_size - 1u;
 
   Lds l;
   {
     unsigned char* p = lds_raw;
     l.sc = reinterpret_cast<unsigned*>(p); p += (size_t)cand_pad * 4;
     l.tok = reinterpret_cast<int*>(p); p += (size_t)cand_pad * 4;
-    l.free_list = reinterpret_cast<unsigned short*>(p); p += (size_t)cand_pad * 2;
-    l.dst = reinterpret_cast<unsigned short*>(p); p += (size_t)cand_pad * 2;
     l.keep = p; p += (size_t)cand_pad;
-    l.cnt = reinterpret_cast<unsigned*>(p); p += (size_t)cand_pad;
-    l.shared = reinterpret_cast<unsigned*>(p);
+    l.hist = reinterpret_cast<unsigned*>(p);
+    l.evicted = reinterpret_cast<unsigned short*>(p);
+    l.free_dst = reinterpret_cast<unsigned short*>(p + (size_t)cand_pad * 2);
+    l.cnt = reinterpret_cast<unsigned*>(p + (size_t)cand_pad * 4);
+    p += select_region_bytes(cand_pad);
+    l.table = reinterpret_cast<unsigned*>(p);
   }
 
-  // ---- scores (sum of the partial column sums in a fixed order) and token indices
-  // Thread t takes candidates t, t + 1024, ...; the partial sums of all of them are fetched
-  // together, eight partials per round, so that many loads are in flight at once.
+  // ---- token indices, the token -> position table of the cached ones, and the scores (sum of
+  // the partial column sums in a fixed order).  Thread t takes candidates t, t + 1024, ...; the
+  // loads of up to four partials of all of them are in flight together, and the first round is
+  // on its way while the table is filled.
   float* scores = a.scores + (size_t)hk * a.cand_stride;
   {
+    int tokv[kMaxItems];
+#pragma unroll
+    for (int i = 0; i < kMaxItems; ++i) {
+      const int p = tid + i * kThreads;
+      tokv[i] = 0;
+      if (i < items && p < n_cand) tokv[i] = p < c ? a.token_idx[(size_t)hk * budget + p] : a.t0 + (p - c);
+    }
     float acc[kMaxItems];
 #pragma unroll
     for (int i = 0; i < kMaxItems; ++i) acc[i] = 0.f;
+    const float* part = a.partial + (size_t)hk * a.n_partials * a.cand_stride;
+    const int n_rounds = a.score_override ? 0 : (a.n_partials + 3) / 4;
+    float v[4][kMaxItems];
+    auto fetch = [&](int round) __attribute__((always_inline)) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = min(4 * round + u, a.n_partials - 1);      // a surplus slot repeats the last partial
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i)
+          if (i < items) v[u][i] = part[(size_t)j * a.cand_stride + min(tid + i * kThreads, n_cand - 1)];
+      }
+    };
+    auto add = [&](int round) __attribute__((always_inline)) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < kMaxItems; ++i)
+          if (i < items && 4 * round + u < a.n_partials) acc[i] += v[u][i];
+    };
+    if (n_rounds > 0) fetch(0);
     if (a.score_override) {
 #pragma unroll
       for (int i = 0; i < kMaxItems; ++i) {
         const int p = tid + i * kThreads;
-        if (p < n_cand) acc[i] = a.score_override[(size_t)hk * n_cand + p];
+        if (i < items && p < n_cand) acc[i] = a.score_override[(size_t)hk * n_cand + p];
       }
-    } else {
-      const float* part = a.partial + (size_t)hk * a.n_partials * a.cand_stride;
-      int j = 0;
-      for (; j + 8 <= a.n_partials; j += 8) {
-        float v[8][kMaxItems];
+    }
+    for (int i = tid; i < a.table_size / 2; i += kThreads) l.table[i] = 0xFFFFFFFFu;
+    if (tid < a.n_segs) {
+      const Seg g = a.segs[tid];
+      SegL sl;
+      sl.begin = g.begin; sl.n = g.n; sl.kind = g.kind; sl.gh = g.gh; sl.gw = g.gw;
+      sl.planes = g.planes; sl.temporal = g.temporal;
+      sl.per = g.gh * g.gw;
+      sl.inv_per = sl.per > 0 ? 1.f / (float)sl.per : 0.f;
+      sl.inv_gw = g.gw > 0 ? 1.f / (float)g.gw : 0.f;
+      s_segs[tid] = sl;
+    }
+    __syncthreads();
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-          for (int i = 0; i < kMaxItems; ++i) {
-            const int p = tid + i * kThreads;
-            v[u][i] = (i < items && p < n_cand) ? part[(size_t)(j + u) * a.cand_stride + p] : 0.f;
-          }
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-          for (int i = 0; i < kMaxItems; ++i) acc[i] += v[u][i];
+    for (int i = 0; i < kMaxItems; ++i) {
+      const int p = tid + i * kThreads;
+      if (i < items && p < n_cand) {
+        l.tok[p] = tokv[i];
+        if (a.merge && p < c) table_insert(l.table, mask, tokv[i], (unsigned)p);
       }
-      for (; j < a.n_partials; ++j)
-#pragma unroll
-        for (int i = 0; i < kMaxItems; ++i) {
-          const int p = tid + i * kThreads;
-          if (p < n_cand) acc[i] += part[(size_t)j * a.cand_stride + p];
-        }
+    }
+    for (int round = 0; round < n_rounds; ++round) {
+      add(round);
+      if (round + 1 < n_rounds) fetch(round + 1);
     }
 #pragma unroll
     for (int i = 0; i < kMaxItems; ++i) {
       const int p = tid + i * kThreads;
-      if (p < n_cand) {
+      if (i < items && p < n_cand) {
         scores[p] = acc[i];
         l.sc[p] = order_bits(acc[i]);
-        l.tok[p] = p < c ? a.token_idx[(size_t)hk * budget + p] : a.t0 + (p - c);
       }
     }
   }
-  if (tid < a.n_segs) {
-    const Seg g = a.segs[tid];
-    SegL sl;
-    sl.begin = g.begin; sl.n = g.n; sl.kind = g.kind; sl.gh = g.gh; sl.gw = g.gw;
-    sl.planes = g.planes; sl.temporal = g.temporal;
-    sl.per = g.gh * g.gw;
-    sl.inv_per = sl.per > 0 ? 1.f / (float)sl.per : 0.f;
-    sl.inv_gw = g.gw > 0 ? 1.f / (float)g.gw : 0.f;
-    s_segs[tid] = sl;
-  }
-  if (tid == 0) s_n_dst = 0;
   __syncthreads();
 
   // ---- own candidates, blocked: thread t owns positions [t * items, (t + 1) * items)
@@ -227,20 +257,20 @@ select_kernel(const SelectArgs a) {
   bool found_unique = false;
   for (int pass = 0; pass < 8 && !found_unique; ++pass) {
     const int shift = 56 - 8 * pass;
-    for (int i = tid; i < 256 * kCopies; i += kThreads) l.shared[i] = 0;
+    for (int i = tid; i < 256 * kCopies; i += kThreads) l.hist[i] = 0;
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kMaxItems; ++i) {
       if (!valid[i]) continue;
       const bool match = pass == 0 || (key[i] >> (shift + 8)) == (prefix >> (shift + 8));
-      if (match) atomicAdd(&l.shared[(unsigned)((key[i] >> shift) & 255u) * kCopies + (lane & (kCopies - 1))], 1u);
+      if (match) atomicAdd(&l.hist[(unsigned)((key[i] >> shift) & 255u) * kCopies + (lane & (kCopies - 1))], 1u);
     }
     __syncthreads();
     {  // bin totals: 4 threads per bin, 8 replicas each
       const int bin = tid >> 2, part = tid & 3;
       unsigned t = 0;
 #pragma unroll
-      for (int k = 0; k < kCopies / 4; ++k) t += l.shared[bin * kCopies + part * (kCopies / 4) + k];
+      for (int k = 0; k < kCopies / 4; ++k) t += l.hist[bin * kCopies + part * (kCopies / 4) + k];
       t += __shfl_xor(t, 1, 64);
       t += __shfl_xor(t, 2, 64);
       if (part == 0) s_bin[bin] = t;
@@ -283,37 +313,40 @@ select_kernel(const SelectArgs a) {
   }
   const unsigned long long threshold = found_unique ? s_threshold : prefix;
 
-  // ---- keep flags; rank free slots and kept block tokens
+  // ---- keep flags; rank the free slots, the kept block tokens and the evicted candidates.
+  // (The histogram is dead from here on: its memory now holds the lists.)
   bool keep[kMaxItems];
-  unsigned n_free = 0, n_new = 0;
+  unsigned n_free = 0, n_new = 0, n_ev = 0;
 #pragma unroll
   for (int i = 0; i < kMaxItems; ++i) {
     const int p = tid * items + i;
     keep[i] = valid[i] && key[i] >= threshold;
     if (valid[i]) {
       l.keep[p] = keep[i];
-      l.dst[p] = kNone16;
       a.keep[(size_t)hk * a.cand_stride + p] = keep[i];
       a.dst[(size_t)hk * a.cand_stride + p] = -1;
       if (p < budget && (p >= c || !keep[i])) ++n_free;
       if (p >= c && keep[i]) ++n_new;
+      if (!keep[i]) ++n_ev;
     }
   }
   unsigned packed = n_free | (n_new << 16);
-  unsigned incl = packed;
+  unsigned incl = packed, incl_ev = n_ev;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const unsigned v = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += v;
+    const unsigned ve = __shfl_up(incl_ev, off, 64);
+    if (lane >= off) { incl += v; incl_ev += ve; }
   }
-  if (lane == 63) s_wave_tot[wave] = incl;
+  if (lane == 63) { s_wave_tot[wave] = incl; s_wave_ev[wave] = incl_ev; }
+  for (int i = tid; i < cand_pad / 4; i += kThreads) l.cnt[i] = 0u;
   __syncthreads();
-  unsigned base = incl - packed;
-  unsigned total = 0;
+  unsigned base = incl - packed, base_ev = incl_ev - n_ev;
+  unsigned total = 0, total_ev = 0;
   for (int w2 = 0; w2 < kWaves; ++w2) {
-    const unsigned t = s_wave_tot[w2];
-    if (w2 < wave) base += t;
-    total += t;
+    const unsigned t = s_wave_tot[w2], te = s_wave_ev[w2];
+    if (w2 < wave) { base += t; base_ev += te; }
+    total += t; total_ev += te;
   }
   unsigned base_free = base & 0xFFFFu, base_new = base >> 16;
   const unsigned total_new = total >> 16;
@@ -323,8 +356,9 @@ select_kernel(const SelectArgs a) {
     const int p = tid * items + i;
     rank_new[i] = -1;
     if (valid[i]) {
-      if (p < budget && (p >= c || !keep[i])) l.free_list[base_free++] = (unsigned short)p;
+      if (p < budget && (p >= c || !keep[i])) l.free_dst[base_free++] = (unsigned short)p;
       if (p >= c && keep[i]) rank_new[i] = (int)base_new++;
+      if (!keep[i]) l.evicted[base_ev++] = (unsigned short)p;
     }
   }
   __syncthreads();
@@ -334,7 +368,7 @@ select_kernel(const SelectArgs a) {
     if (rank_new[i] >= 0) {
       MoveEntry e;
       e.pos = tid * items + i;
-      e.slot = l.free_list[rank_new[i]];
+      e.slot = l.free_dst[rank_new[i]];
       e.stage = -1;
       e.pad = 0;
       moves[rank_new[i]] = e;
@@ -346,46 +380,61 @@ select_kernel(const SelectArgs a) {
     if (tid == 0) a.counts[hk].n_dst = 0;
     return;
   }
+  __syncthreads();                       // the free list has been consumed: it now takes destinations
 
-  // ---- merge plan
-  const unsigned mask = (unsigned)a.table_size - 1u;
-  for (int i = tid; i < a.table_size / 2; i += kThreads) l.shared[i] = 0xFFFFFFFFu;
-  for (int i = tid; i < cand_pad / 4; i += kThreads) l.cnt[i] = 0u;
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < kMaxItems; ++i) {
-    const int p = tid * items + i;
-    if (valid[i] && p < c) table_insert(l.shared, mask, l.tok[p], (unsigned)p);
-  }
-  __syncthreads();
-  // every evicted visual candidate picks its best kept neighbour and counts itself in there
-#pragma unroll
-  for (int i = 0; i < kMaxItems; ++i) {
-    if (!valid[i] || keep[i]) continue;
-    const int p = tid * items + i;
-    int nb[kNeighbours];
-    if (!neighbours(s_segs, a.n_segs, l.tok[p], nb)) continue;
-    int r[kNeighbours];
-#pragma unroll
-    for (int j = 0; j < kNeighbours; ++j) r[j] = nb[j] >= 0 ? find_pos(l, mask, nb[j], c, n, a.t0) : -1;
-    unsigned long long best_key = 0;
+  // ---- merge plan: the e-th evicted candidate (thread e, e + 1024, ...) picks its best kept
+  // grid neighbour and counts itself in there
+  for (unsigned e = tid; e < total_ev; e += kThreads) {
+    const int p = l.evicted[e];
+    const int tokp = l.tok[p];
     int best = -1;
+    int nb[kNeighbours];
+    if (neighbours(s_segs, a.n_segs, tokp, nb)) {
+      // first probe of all neighbours at once; a token of the block sits at a known position
+      unsigned h[kNeighbours], ent[kNeighbours];
+      bool in_block[kNeighbours];
 #pragma unroll
-    for (int j = 0; j < kNeighbours; ++j) {
-      if (r[j] < 0 || !l.keep[r[j]]) continue;
-      const unsigned long long kr = make_key(l.sc[r[j]], l.tok[r[j]]);
-      if (best < 0 || kr > best_key) { best = r[j]; best_key = kr; }
+      for (int j = 0; j < kNeighbours; ++j) {
+        in_block[j] = nb[j] >= a.t0 && nb[j] < a.t0 + n;
+        h[j] = hash_tok(nb[j] < 0 ? 0 : nb[j], mask);
+        ent[j] = table_entry(l, h[j]);
+      }
+      int r[kNeighbours];
+      int tk[kNeighbours];
+#pragma unroll
+      for (int j = 0; j < kNeighbours; ++j) {
+        r[j] = in_block[j] ? c + (nb[j] - a.t0) : (ent[j] == kNone16 ? -1 : (int)ent[j]);
+        tk[j] = r[j] >= 0 ? l.tok[r[j]] : -1;
+      }
+#pragma unroll
+      for (int j = 0; j < kNeighbours; ++j) {
+        if (nb[j] < 0) r[j] = -1;
+        else if (!in_block[j] && r[j] >= 0 && tk[j] != nb[j]) r[j] = probe_on(l, mask, nb[j], h[j], ent[j]);
+      }
+      unsigned kp[kNeighbours], sc[kNeighbours];
+#pragma unroll
+      for (int j = 0; j < kNeighbours; ++j) {
+        kp[j] = r[j] >= 0 ? l.keep[r[j]] : 0u;
+        sc[j] = r[j] >= 0 ? l.sc[r[j]] : 0u;
+      }
+      unsigned long long best_key = 0;
+#pragma unroll
+      for (int j = 0; j < kNeighbours; ++j) {
+        if (!kp[j]) continue;
+        const unsigned long long kr = make_key(sc[j], nb[j]);
+        if (best < 0 || kr > best_key) { best = r[j]; best_key = kr; }
+      }
     }
+    l.free_dst[e] = best >= 0 ? (unsigned short)best : (unsigned short)kNone16;
     if (best >= 0) {
-      l.dst[p] = (unsigned short)best;
       a.dst[(size_t)hk * a.cand_stride + p] = best;
       atomicAdd(&l.cnt[best >> 2], 1u << (8 * (best & 3)));
     }
   }
   __syncthreads();
-  // number the destinations that were chosen, in candidate order
-  unsigned short* jmap = l.free_list;                       // the free list has been consumed
-  unsigned* fill = reinterpret_cast<unsigned*>(l.keep);     // so have the keep flags
+  // number the destinations that were chosen, in candidate order; the ordinal of a destination
+  // goes where its score bits were (nobody reads those any more)
+  unsigned* fill = reinterpret_cast<unsigned*>(l.keep);     // the keep flags have been consumed
   unsigned n_mine = 0;
   unsigned cnt_of[kMaxItems];
 #pragma unroll
@@ -400,7 +449,6 @@ select_kernel(const SelectArgs a) {
     const unsigned v = __shfl_up(incl2, off, 64);
     if (lane >= off) incl2 += v;
   }
-  __syncthreads();                       // everybody has read keep[] and cnt[]; s_wave_tot is free
   if (lane == 63) s_wave_tot[wave] = incl2;
   for (int i = tid; i < cand_pad / 4; i += kThreads) fill[i] = 0u;
   __syncthreads();
@@ -415,7 +463,7 @@ select_kernel(const SelectArgs a) {
   for (int i = 0; i < kMaxItems; ++i) {
     if (!cnt_of[i]) continue;
     const int p = tid * items + i;
-    jmap[p] = (unsigned short)ord;
+    l.sc[p] = ord;
     dsts[ord].pos = p;
     dsts[ord].n_src = (int)cnt_of[i];
     if (rank_new[i] >= 0) moves[rank_new[i]].stage = (int)ord;
@@ -423,15 +471,12 @@ select_kernel(const SelectArgs a) {
   }
   __syncthreads();
   // every source writes itself into its destination's entry
-#pragma unroll
-  for (int i = 0; i < kMaxItems; ++i) {
-    if (!valid[i] || keep[i]) continue;
-    const int p = tid * items + i;
-    const unsigned d = l.dst[p];
+  for (unsigned e = tid; e < total_ev; e += kThreads) {
+    const unsigned d = l.free_dst[e];
     if (d == kNone16) continue;
     const unsigned old = atomicAdd(&fill[d >> 2], 1u << (8 * (d & 3)));
     const unsigned k = (old >> (8 * (d & 3))) & 0xFFu;
-    dsts[jmap[d]].src[k] = p;
+    dsts[l.sc[d]].src[k] = l.evicted[e];
   }
   if (tid == 0) a.counts[hk].n_dst = (int)n_dst;
 }
@@ -440,10 +485,7 @@ select_kernel(const SelectArgs a) {
 
 size_t select_lds_bytes(int /*n_cand*/, int items, int table_size) {
   const size_t cand_pad = (size_t)items * kThreads;
-  size_t shared = (size_t)256 * kCopies * 4;
-  const size_t table = (size_t)table_size * 2;
-  if (table > shared) shared = table;
-  return cand_pad * (4 + 4 + 2 + 2 + 1 + 1) + shared;
+  return cand_pad * (4 + 4 + 1) + select_region_bytes(cand_pad) + (size_t)table_size * 2;
 }
 
 hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s) {
