@@ -26,7 +26,7 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxItems = KVP_MAX_CANDIDATES / kThreads;   // 8
+constexpr int kMaxItemsAny = KVP_MAX_CANDIDATES / kThreads;   // 8
 constexpr int kCopies = 32;                                // histogram replicas
 constexpr unsigned kNone16 = 0xFFFFu;
 
@@ -133,6 +133,9 @@ __device__ __forceinline__ bool neighbours(const SegL* segs, int n_segs, int tok
   return false;
 }
 
+// kMaxItems: candidates a thread can own (4 covers up to 4096 candidates and halves the registers
+// of the batched loads; 8 covers the limit)
+template <int kMaxItems>
 __global__ void __launch_bounds__(kThreads)
 select_kernel(const SelectArgs a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -140,6 +143,7 @@ select_kernel(const SelectArgs a) {
   __shared__ unsigned s_digit, s_want, s_bin_count;
   __shared__ unsigned s_bin[256];
   __shared__ unsigned s_wave_tot[kWaves], s_wave_ev[kWaves];
+  __shared__ unsigned s_wave_diff[2 * kWaves];
   __shared__ SegL s_segs[KVP_MAX_SEGMENTS];
 
   const int hk = blockIdx.x;
@@ -165,7 +169,7 @@ select_kernel(const SelectArgs a) {
 
   // ---- token indices, the token -> position table of the cached ones, and the scores (sum of
   // the partial column sums in a fixed order).  Thread t takes candidates t, t + 1024, ...; the
-  // loads of up to four partials of all of them are in flight together, and the first round is
+  // loads of a batch of partials of all of them are in flight together, and the first batch is
   // on its way while the table is filled.
   float* scores = a.scores + (size_t)hk * a.cand_stride;
   {
@@ -180,12 +184,13 @@ select_kernel(const SelectArgs a) {
 #pragma unroll
     for (int i = 0; i < kMaxItems; ++i) acc[i] = 0.f;
     const float* part = a.partial + (size_t)hk * a.n_partials * a.cand_stride;
-    const int n_rounds = a.score_override ? 0 : (a.n_partials + 3) / 4;
-    float v[4][kMaxItems];
+    constexpr int kBatch = kMaxItems <= 4 ? 8 : 4;             // partials fetched together
+    const int n_rounds = a.score_override ? 0 : (a.n_partials + kBatch - 1) / kBatch;
+    float v[kBatch][kMaxItems];
     auto fetch = [&](int round) __attribute__((always_inline)) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int j = min(4 * round + u, a.n_partials - 1);      // a surplus slot repeats the last partial
+      for (int u = 0; u < kBatch; ++u) {
+        const int j = min(kBatch * round + u, a.n_partials - 1);      // a surplus slot repeats the last partial
 #pragma unroll
         for (int i = 0; i < kMaxItems; ++i)
           if (i < items) v[u][i] = part[(size_t)j * a.cand_stride + min(tid + i * kThreads, n_cand - 1)];
@@ -193,10 +198,10 @@ select_kernel(const SelectArgs a) {
     };
     auto add = [&](int round) __attribute__((always_inline)) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < kBatch; ++u)
 #pragma unroll
         for (int i = 0; i < kMaxItems; ++i)
-          if (i < items && 4 * round + u < a.n_partials) acc[i] += v[u][i];
+          if (i < items && kBatch * round + u < a.n_partials) acc[i] += v[u][i];
     };
     if (n_rounds > 0) fetch(0);
     if (a.score_override) {
@@ -251,26 +256,52 @@ select_kernel(const SelectArgs a) {
     key[i] = valid[i] ? make_key(l.sc[p], l.tok[p]) : 0ull;
   }
 
-  // ---- radix select of the budget-th largest key
-  unsigned long long prefix = 0;
+  // ---- radix select of the budget-th largest key, eight bits at a time, starting at the highest
+  // bit in which any two keys differ (float scores share their sign and most of the exponent,
+  // and digits spent on a common prefix would tell nothing apart)
+  // (the bits in which some key differs from candidate 0 are the bits in which any two differ)
+  const unsigned long long ref = make_key(l.sc[0], l.tok[0]);
+  unsigned diff_hi = 0, diff_lo = 0;
+#pragma unroll
+  for (int i = 0; i < kMaxItems; ++i)
+    if (valid[i]) {
+      diff_hi |= (unsigned)((key[i] ^ ref) >> 32);
+      diff_lo |= (unsigned)(key[i] ^ ref);
+    }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    diff_hi |= __shfl_xor(diff_hi, off, 64);
+    diff_lo |= __shfl_xor(diff_lo, off, 64);
+  }
+  if (lane == 0) { s_wave_diff[2 * wave] = diff_hi; s_wave_diff[2 * wave + 1] = diff_lo; }
+  __syncthreads();
+#pragma unroll
+  for (int w2 = 0; w2 < kWaves; ++w2) { diff_hi |= s_wave_diff[2 * w2]; diff_lo |= s_wave_diff[2 * w2 + 1]; }
+  const unsigned long long diff = ((unsigned long long)diff_hi << 32) | diff_lo;
+  int top = diff ? 64 - __builtin_clzll(diff) : 0;             // bits [0, top) are still undecided
+  unsigned long long prefix = top >= 64 ? 0ull : (ref >> top) << top;
   unsigned want = (unsigned)budget;
   bool found_unique = false;
-  for (int pass = 0; pass < 8 && !found_unique; ++pass) {
-    const int shift = 56 - 8 * pass;
+  while (top > 0 && !found_unique) {
+    const int width = top < 8 ? top : 8;
+    const int lo = top - width;
     for (int i = tid; i < 256 * kCopies; i += kThreads) l.hist[i] = 0;
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kMaxItems; ++i) {
       if (!valid[i]) continue;
-      const bool match = pass == 0 || (key[i] >> (shift + 8)) == (prefix >> (shift + 8));
-      if (match) atomicAdd(&l.hist[(unsigned)((key[i] >> shift) & 255u) * kCopies + (lane & (kCopies - 1))], 1u);
+      const bool match = top >= 64 || (key[i] >> top) == (prefix >> top);
+      if (match)
+        atomicAdd(&l.hist[(unsigned)((key[i] >> lo) & ((1u << width) - 1u)) * kCopies + (lane & (kCopies - 1))], 1u);
     }
     __syncthreads();
-    {  // bin totals: 4 threads per bin, 8 replicas each
+    {  // bin totals: 4 threads per bin, 8 replicas each, taken in an order that keeps the 64 lanes
+       // of a wave on 64 different banks (bin b, replica r is word 32 b + r)
       const int bin = tid >> 2, part = tid & 3;
       unsigned t = 0;
 #pragma unroll
-      for (int k = 0; k < kCopies / 4; ++k) t += l.hist[bin * kCopies + part * (kCopies / 4) + k];
+      for (int k = 0; k < kCopies / 4; ++k)
+        t += l.hist[bin * kCopies + ((4 * (bin >> 1) + part + 4 * k) & (kCopies - 1))];
       t += __shfl_xor(t, 1, 64);
       t += __shfl_xor(t, 2, 64);
       if (part == 0) s_bin[bin] = t;
@@ -300,16 +331,17 @@ select_kernel(const SelectArgs a) {
       }
     }
     __syncthreads();
-    prefix |= (unsigned long long)s_digit << shift;
+    prefix |= (unsigned long long)s_digit << lo;
     want = s_want;
     if (s_bin_count == 1) {
       // the bin holds exactly the key we are after
 #pragma unroll
       for (int i = 0; i < kMaxItems; ++i)
-        if (valid[i] && (key[i] >> shift) == (prefix >> shift)) s_threshold = key[i];
+        if (valid[i] && (key[i] >> lo) == (prefix >> lo)) s_threshold = key[i];
       found_unique = true;
     }
     __syncthreads();
+    top = lo;
   }
   const unsigned long long threshold = found_unique ? s_threshold : prefix;
 
@@ -490,14 +522,17 @@ size_t select_lds_bytes(int /*n_cand*/, int items, int table_size) {
 
 hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s) {
   const size_t lds = select_lds_bytes(a.c + a.n, a.items, a.table_size);
-  static size_t attr_bytes = 0;
-  if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  const bool small = a.items <= 4;
+  const void* fn = small ? reinterpret_cast<const void*>(select_kernel<4>)
+                         : reinterpret_cast<const void*>(select_kernel<kMaxItemsAny>);
+  static size_t attr_bytes[2] = {0, 0};
+  if (lds > attr_bytes[small]) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_bytes = lds;
+    attr_bytes[small] = lds;
   }
-  hipLaunchKernelGGL(select_kernel, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
+  if (small) hipLaunchKernelGGL(select_kernel<4>, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
+  else hipLaunchKernelGGL(select_kernel<kMaxItemsAny>, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
   return hipGetLastError();
 }
 
