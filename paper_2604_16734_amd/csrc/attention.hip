@@ -265,7 +265,9 @@ attention_kernel(const AttnArgs a) {
 
     // Hide block keys a row may not see, fix the reference at the first visible block, and
     // watch for a block maximum far above the reference.
-    auto prepare = [&](f32x16 (&s)[QT], int kb, auto mask) __attribute__((always_inline)) {
+    // `track` is off for the tiles after the first plain one: every row has its reference by
+    // then, and a logit far above it shows up in the row sum instead (checked after the loop).
+    auto prepare = [&](f32x16 (&s)[QT], int kb, auto mask, auto track) __attribute__((always_inline)) {
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
         if constexpr (decltype(mask)::value) {
@@ -274,12 +276,14 @@ attention_kernel(const AttnArgs a) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) s[t][r] = (8 * (r >> 2) + (r & 3) <= lim) ? s[t][r] : -INFINITY;
         }
-        float v = s[t][0];
+        if constexpr (decltype(track)::value) {
+          float v = s[t][0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) v = fmaxf(v, s[t][r]);
-        const float mx = max_with_other_half(v);
-        m_ref[t] = (m_ref[t] == -INFINITY) ? mx : m_ref[t];
-        redo |= mx > m_ref[t] + redo_raw;
+          for (int r = 1; r < 16; ++r) v = fmaxf(v, s[t][r]);
+          const float mx = max_with_other_half(v);
+          m_ref[t] = (m_ref[t] == -INFINITY) ? mx : m_ref[t];
+          redo |= mx > m_ref[t] + redo_raw;
+        }
       }
     };
 
@@ -390,7 +394,7 @@ attention_kernel(const AttnArgs a) {
 
     // kTag = t & 1 as a compile-time constant in the steady-state loop, -1 for "use t & 1".
     // The steady-state loop also knows that the tiles it prefetches are uniform.
-    auto body = [&](int t, auto buf_tag, auto mask) __attribute__((always_inline)) {
+    auto body = [&](int t, auto buf_tag, auto mask, auto track) __attribute__((always_inline)) {
       constexpr int kTag = decltype(buf_tag)::value;
       const int buf = kTag >= 0 ? kTag : (t & 1);
       const int kb = t * S::kTk + ks * 64;
@@ -399,13 +403,13 @@ attention_kernel(const AttnArgs a) {
       u16* v_cur = lds_v + buf * S::kTile;
       u16* v_prv = lds_v + (buf ^ 1) * S::kTile;
       // ---- phase 1: P_X(t), S_Y(t), O += P_Y(t-1) V(t-1)
-      prepare(sx, kb, mask);
+      prepare(sx, kb, mask, track);
       phase_core(sx, px, sy, k_cur + blk_off + 32 * D, py, v_prv + blk_off + 32 * D, [](auto, int) {});
       wait_loads();               // the loads this wave issued in the last phase 2 have landed
       __syncthreads();
       // ---- phase 2: P_Y(t), S_X(t+1), O += P_X(t) V(t); the loads of K(t+2) and V(t+1) are spread
       // over the matrix instructions so that their issue does not stall the wave in one burst
-      prepare(sy, kb + 32, mask);
+      prepare(sy, kb + 32, mask, track);
       constexpr int kPerHalf = QT * (D / 16);              // MFMAs in each half of a phase
       constexpr int kEvery = kPerHalf / S::kLoadsPerWave;  // one load every kEvery MFMAs
       static_assert(kEvery >= 1 && kPerHalf % S::kLoadsPerWave == 0, "loads must fit the phase");
@@ -437,11 +441,18 @@ attention_kernel(const AttnArgs a) {
            tile_is_uniform(n_fast + 3))
       n_fast += 2;
     int t = 0;
-    for (; t < n_fast; t += 2) {
-      body(t, Even{}, std::false_type{});
-      body(t + 1, Odd{}, std::false_type{});
+    if (n_fast >= 2) {
+      // tile 0 is plain: it gives every row its reference
+      body(0, Even{}, std::false_type{}, std::true_type{});
+      body(1, Odd{}, std::false_type{}, std::true_type{});
+      t = 2;
     }
-    for (; t < n_tiles; ++t) body(t, Any{}, std::true_type{});   // masking a fully visible tile is harmless
+    for (; t < n_fast; t += 2) {
+      body(t, Even{}, std::false_type{}, std::false_type{});
+      body(t + 1, Odd{}, std::false_type{}, std::false_type{});
+    }
+    for (; t < n_tiles; ++t)       // masking a fully visible tile is harmless
+      body(t, Any{}, std::true_type{}, std::true_type{});
     wait_loads();
     __syncthreads();               // V of the last tile has landed for everybody
     {
@@ -458,6 +469,10 @@ attention_kernel(const AttnArgs a) {
         }
       }
     }
+    // a logit more than 2^64 above its row's reference in a tile that did not track maxima has
+    // pushed the row sum past 2^64 (or to infinity or NaN)
+#pragma unroll
+    for (int tq = 0; tq < QT; ++tq) redo |= !(l_run[tq] <= 0x1p64f);
     redo = __syncthreads_or(redo) != 0;     // workgroup-uniform; also: everybody is done with the tiles
 
     if (!redo) {

@@ -109,13 +109,15 @@ def test_scores_and_free_selection(hq, hkv, d, c, n, budget, chunk_max, scale):
     cache.close()
 
 
-@pytest.mark.parametrize("hq,hkv,d,c,n", [(4, 2, 64, 100, 150), (8, 2, 128, 256, 300), (4, 4, 128, 0, 96)])
+@pytest.mark.parametrize("hq,hkv,d,c,n", [(4, 2, 64, 100, 150), (8, 2, 128, 256, 300), (4, 4, 128, 0, 96),
+                                          (8, 2, 128, 1280, 300),    # the runaway shows up in tiles that no longer track maxima
+                                          (32, 8, 128, 1536, 1024)])  # ... and in the eight-wave shape
 def test_runaway_logits_take_the_careful_path(hq, hkv, d, c, n):
     """Logits that climb by hundreds of nats along the keys: the fixed softmax reference of the
     fast loop would overflow, so the kernel must detect it and redo the rows exactly."""
     from kvp_workload import f32_to_bf16_bits
     rng = np.random.default_rng(d + c)
-    budget, chunk_max = 4096, 512
+    budget, chunk_max = 4096, max(512, n)
     segs = [Segment(0, 100000, 0)]
     cache = K.Cache(1, hq, hkv, d, budget, chunk_max, segs, merge=False, device=DEV)
     tot = c + n
