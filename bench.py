@@ -59,32 +59,34 @@ def generate(wl, device, threads):
     return out
 
 
-def run_steps(cache, wl, data, ranges, steps, outs):
+def run_steps(driver, cache, wl, data, ranges, steps, outs):
+    """`steps` whole prefills: every block through every layer, in the order `driver` gives
+    (compactions in line, or on a second stream beside the following layers' attention)."""
     for _ in range(steps):
         for layer in range(wl.n_layers):
             cache.set_state(layer, 0, 0)
         for t0, n in ranges:
-            for layer in range(wl.n_layers):
-                q, k, v = data[layer]
-                cache.prefill_chunk(layer, t0, q[t0:t0 + n], k[t0:t0 + n], v[t0:t0 + n], out=outs[layer][:n])
-                cache.compact(layer)
+            driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n])
+    driver.finish()
 
 
-def bench_workload(wl, steps, warmup, device, threads, profile=True):
+def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1):
     import torch
     import paper_2604_16734_amd as K
     from kvp_workload import chunk_ranges
 
     data = generate(wl, device, threads)
     ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    two = streams == 2 and wl.n_layers >= 4
     cache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
-                    wl.segments, merge=True, scratch_sets=1, device=device)
+                    wl.segments, merge=True, scratch_sets=2 if two else 1, device=device)
+    driver = K.Prefill(cache, wl.n_layers, overlap=two)
     outs = [torch.empty((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=device)
             for _ in range(wl.n_layers)]
-    run_steps(cache, wl, data, ranges, warmup, outs)
+    run_steps(driver, cache, wl, data, ranges, warmup, outs)
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
-    run_steps(cache, wl, data, ranges, steps, outs)
+    run_steps(driver, cache, wl, data, ranges, steps, outs)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
     ms_per_step = 1e3 * elapsed / steps
@@ -101,7 +103,9 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True):
         cache.profile_enable(True)
         torch.cuda.synchronize()
         t_begin = time.perf_counter()
-        run_steps(cache, wl, data, ranges, prof_steps, outs)
+        # per-kernel times are taken with everything in line on one stream: beside another
+        # kernel a launch takes longer than it needs
+        run_steps(K.Prefill(cache, wl.n_layers, overlap=False), cache, wl, data, ranges, prof_steps, outs)
         torch.cuda.synchronize()
         res["profiled_ms_per_step"] = 1e3 * (time.perf_counter() - t_begin) / prof_steps
         stats = cache.profile_read()
@@ -182,6 +186,8 @@ def main():
     ap.add_argument("--workload", default="long_video")
     ap.add_argument("--others", type=int, default=1, help="also time the other four shapes (few steps)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2: kvp_compact of a layer runs on a second stream beside the next layers' kvp_prefill_chunk")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -205,13 +211,13 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-    main_res = bench_workload(wl, args.steps, args.warmup, device, threads)
+    main_res = bench_workload(wl, args.steps, args.warmup, device, threads, streams=args.streams)
 
     others = {}
     if args.others:
         for w in WORKLOADS:
             if w.name != wl.name:
-                r = bench_workload(w, max(3, args.steps // 2), 2, device, threads, profile=True)
+                r = bench_workload(w, max(3, args.steps // 2), 2, device, threads, profile=True, streams=args.streams)
                 others[w.name] = {
                     "tokens_per_s": round(r["tokens_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4),
                     "attention_tflops": round(r["attention_tflops"], 2),

@@ -12,3 +12,4 @@ from .binding import (  # noqa: F401
     kvp_profile_read, kvp_kernel_name, kvp_free_cache,
     Cache,
 )
+from .runtime import Prefill  # noqa: F401

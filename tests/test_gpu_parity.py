@@ -284,3 +284,36 @@ def test_free_running_invariants(name):
     for layer in layers:      # two runs agree bit for bit: no atomics on floats anywhere
         assert np.array_equal(results[0][layer][0], results[1][layer][0])
         assert np.array_equal(results[0][layer][1], results[1][layer][1])
+
+
+@pytest.mark.parametrize("name", ["tiled_image", "video"])
+def test_compaction_on_a_second_stream_changes_nothing(name):
+    """The whole prefill with every kvp_compact on a second stream (two scratch sets, events
+    between the streams) must leave bit for bit the caches and outputs of the in-order run."""
+    wl = get_workload(name)
+    layers = min(wl.n_layers, 6)
+    data = [tuple(U.bits_to_torch(x) for x in layer_inputs(wl, l)) for l in range(layers)]
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    results = []
+    for overlap in (False, True):
+        cache = K.Cache(layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments,
+                        merge=True, scratch_sets=2 if overlap else 1, device=DEV)
+        driver = K.Prefill(cache, layers, overlap=overlap)
+        outs = [torch.zeros((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=DEV)
+                for _ in range(layers)]
+        for t0, n in ranges:
+            driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n])
+        driver.finish()
+        torch.cuda.synchronize()
+        state = []
+        for l in range(layers):
+            k, v, idx, w, count, nxt = cache.decode_ready(l)
+            state.append((k[:, :count].clone(), v[:, :count].clone(), idx[:, :count].clone(), w[:, :count].clone(),
+                          count, nxt, outs[l].clone()))
+        results.append(state)
+        cache.close()
+    for a, b in zip(*results):
+        assert a[4] == b[4] and a[5] == b[5]
+        for x, y in zip(a[:4] + (a[6],), b[:4] + (b[6],)):
+            assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                               y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
