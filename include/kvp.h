@@ -7,8 +7,9 @@
  * and every layer the caller makes two calls:
  *
  *   kvp_prefill_chunk   the block's queries attend over cache U block
- *                       (Eq. 1, Sec. 2.1) and every candidate key receives
- *                       its importance score (Eq. 4, Sec. 3.2);
+ *                       (Eq. 1, Sec. 2.1) and, when the block will not fit
+ *                       into the budget, every candidate key receives its
+ *                       importance score (Eq. 4, Sec. 3.2);
  *   kvp_compact         the block is appended to the cache (Alg. 1 line 7)
  *                       and, if the cache now exceeds M, the lowest-scored
  *                       entries are evicted until it holds M (lines 8-11).
@@ -161,8 +162,9 @@ int kvp_set_state(kvp_cache* cache, int32_t layer, int32_t count, int32_t next_t
 /* Inspection of the last block of a layer (device pointers, valid until the
  * layer's scratch set is reused).  n_cand = c + n of that block; candidates are
  * cache slots 0..c-1 then block tokens.
- *   scores [n_kv_heads, *stride]  fp32, valid after kvp_prefill_chunk
- *                                 (after kvp_compact they hold the scores used)
+ *   scores [n_kv_heads, *stride]  fp32, valid after a kvp_compact that had to evict
+ *                                 (c + n > budget): the scores it used.  A block that
+ *                                 fits into the cache is appended without being scored.
  *   keep   [n_kv_heads, *stride]  uint8, valid after kvp_compact
  *   dst    [n_kv_heads, *stride]  int32 candidate position merged into, or -1
  * Any out-pointer may be NULL. */

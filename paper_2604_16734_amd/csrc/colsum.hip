@@ -23,9 +23,9 @@
 //
 // Query tiles go from global memory straight into a ring of LDS buffers
 // (global_load_lds, 16-byte chunks XOR-swizzled by row so that the fragment
-// reads are conflict-free), three tiles ahead of their use; the loads are
-// issued as inline assembly and ordered by hand (a counted s_waitcnt before the
-// barrier that publishes a tile) so that later tiles stay in flight.
+// reads are conflict-free), a pair of tiles at a time while the pair before it is
+// in use; the loads are issued as inline assembly and waited for by hand, one
+// barrier per pair.
 //
 // Work split: a workgroup owns one block of keys of one KV head and a range of
 // query tiles.  Key blocks that lie in the new part of the candidates are seen
@@ -46,8 +46,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int kRing = 4;               // LDS query-tile buffers
-constexpr int kAhead = 3;              // tiles in flight ahead of the one in use
+constexpr int kRing = 4;               // LDS query-tile buffers: the pair of tiles in use and the pair in flight
 constexpr int kStatRing = 8;           // row statistics stay one step longer than their tile: a longer ring
 constexpr int kMaxRowSplits = 16;
 
@@ -60,7 +59,6 @@ colsum_kernel(const ColsumArgs a) {
   constexpr int kRowsPerInstr = 64 / kChunks;      // rows one 1 KiB load instruction brings in
   constexpr int kInstrPerTile = 32 / kRowsPerInstr;
   constexpr int kQLoads = kInstrPerTile > W ? kInstrPerTile / W : 1;   // 1 KiB pieces per wave and tile
-  constexpr int kLoadsPerStep = kQLoads + 1;                           // plus the row statistics
   constexpr int kWaveKeys = 32 * NT;
   constexpr int kBlockKeys = W * kWaveKeys;
   constexpr int kMfmas = NT * (D / 16);            // per wave and tile
@@ -128,8 +126,8 @@ colsum_kernel(const ColsumArgs a) {
     else if (iq_head + 1 < group) { ++iq_head; iq_tile = 0; }
   };
   if (n_steps > 0) {
-#pragma unroll
-    for (int i = 0; i < kAhead; ++i) issue_step();
+    issue_step();
+    issue_step();
   }
 
   // ---- this wave's keys: B operand, lane holds K[key0 + 32 t + l32][16 s + 8 g .. + 7]
@@ -171,12 +169,13 @@ colsum_kernel(const ColsumArgs a) {
   float sl2_masked;
   asm volatile("v_mov_b32 %0, %1" : "=v"(sl2_masked) : "s"(sl2));
 
-  // tile i has landed for this wave when at most the loads of the (kAhead - 1) later tiles remain
-  // ... and for everybody after the barrier; everybody has also read tile i - 1 by then, so its
-  // buffer takes tile i + kAhead.  A bare s_barrier on purpose: __syncthreads() carries a fence
-  // that drains ALL loads in flight, which would throw the prefetch ring away at every step.
+  // Tiles are published in pairs, one barrier for two stages: the pair has landed for this wave
+  // when none of its loads remain ... and for everybody after the barrier; everybody has also
+  // read the pair before by then, so its buffers take the next pair.  A bare s_barrier on
+  // purpose: __syncthreads() carries a fence the compiler places waits around.
   auto publish = [&]() __attribute__((always_inline)) {
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((kAhead - 1) * kLoadsPerStep) : "memory");
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    issue_step();
     issue_step();
   };
   // S of the tile in ring buffer BUF for this wave's keys
@@ -233,7 +232,7 @@ colsum_kernel(const ColsumArgs a) {
   // tile before it (first row `row0`, statistics in `slot`) from `sp`
   auto stage = [&](auto buf_c, int row0, int slot, const f32x16 (&sp)[NT], f32x16 (&sn)[NT])
       __attribute__((always_inline)) {
-    publish();
+    if (decltype(buf_c)::value % 2 == 0) publish();
     constexpr int kElemsPerMfma = 16 * NT / kMfmas;       // 2 (D = 128) or 4 (D = 64)
     constexpr int kFragsAhead = 4;                         // operand fragments read before the first MFMA
     float ls[16];

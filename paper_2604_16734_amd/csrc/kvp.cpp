@@ -354,9 +354,12 @@ int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t 
   cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
   cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
   cs.scale_log2 = aa.scale_log2;
-  plan_colsum(cs, cfg.head_dim);
-  rc = launch(c, KVP_K_COLSUM, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
-  if (rc) return rc;
+  // the scores decide an eviction; a block that fits into the cache as it is needs none
+  if (L.count + n_tokens > cfg.budget) {
+    plan_colsum(cs, cfg.head_dim);
+    rc = launch(c, KVP_K_COLSUM, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
+    if (rc) return rc;
+  }
 
   L.state = PENDING;
   L.t0 = token_begin; L.n = n_tokens;
