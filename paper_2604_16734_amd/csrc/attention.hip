@@ -167,7 +167,11 @@ attention_kernel(const AttnArgs a) {
   const int ld_sub = lane / S::kChunks, ld_pos = lane % S::kChunks;
   const int ld_row = S::kRowsPerLoad * wave + ld_sub;          // + kRowGroup j
   const int ld_chunk_k = ld_pos ^ (ld_row % S::kChunks);
-  const int ld_chunk_v = ld_pos ^ (2 * (ld_row % (S::kChunks / 2)));
+  // V rows are read four at a time by each half of a wave (transposing 8-byte reads, 64 bytes
+  // of each row): the swizzle sends those four 64-byte pieces to four different quarters of the
+  // 64 banks (D = 128: a row spans all banks; D = 64: rows r and r + 2 share their banks)
+  auto v_swizzle = [](int row) { return 4 * ((row % 4) >> (D == 64 ? 1 : 0)); };
+  const int ld_chunk_v = ld_pos ^ v_swizzle(ld_row);
   auto lds_dst = [&](u16* tile, int j) __attribute__((always_inline)) -> u16* {
     return tile + (S::kRowGroup * j + S::kRowsPerLoad * wave) * D;     // wave-uniform
   };
@@ -222,7 +226,7 @@ attention_kernel(const AttnArgs a) {
   int v_off[D / 32];
   {
     const int rsub = 4 * g + ((lane & 15) >> 2);
-    const int z = 2 * (rsub % (S::kChunks / 2));
+    const int z = v_swizzle(rsub);
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt) {
       const int chunk = (4 * dt + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ z;
@@ -352,14 +356,23 @@ attention_kernel(const AttnArgs a) {
       }
 #pragma unroll
       for (int t = 0; t < QT; ++t) l_run[t] += sum[t];
-      // pipeline: one MFMA, one LDS read while any remain, then the vector work of its elements
+      // pipeline: the first kAhead operand reads, then per MFMA the read(s) of the operand kAhead
+      // further on (one 16-byte read for a K fragment, two transposing reads for a V^T fragment;
+      // an operand serves QT MFMAs) and the vector work of its elements
       constexpr int kMfmas = QT * (kNK + kNV);
-      constexpr int kReads = kNK + 2 * kNV - kAhead;      // the first kAhead reads go ahead of everything
+      __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
       for (int i = 0; i < kMfmas; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
-        if (i < kReads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // LDS read
-        __builtin_amdgcn_sched_group_barrier(0x002, 5 * kPerMfma, 0);           // VALU (incl. exp)
+        if (i % QT == 0) {
+          const int next = i / QT + kAhead;                                     // operand to fetch now
+          if (next < kNK) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          else if (next < kNK + kNV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        // per element: scale-and-shift, add to the row sum, half a pack to bf16; and the exponential
+        if (i & 1) __builtin_amdgcn_sched_group_barrier(0x002, (5 * kPerMfma + 1) / 2, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x002, (5 * kPerMfma) / 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, kPerMfma, 0);
       }
     };
 
@@ -405,6 +418,13 @@ attention_kernel(const AttnArgs a) {
       // ---- phase 1: P_X(t), S_Y(t), O += P_Y(t-1) V(t-1)
       prepare(sx, kb, mask, track);
       phase_core(sx, px, sy, k_cur + blk_off + 32 * D, py, v_prv + blk_off + 32 * D, [](auto, int) {});
+      // P_X is only read in phase 2, and the compiler would gladly take its exponentials there,
+      // all in a lump behind the barrier: make them due here, in the shadow of this phase's MFMAs
+#pragma unroll
+      for (int tq = 0; tq < QT; ++tq)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) asm volatile("" ::"v"(px[tq][r]));
+      __builtin_amdgcn_sched_barrier(0);
       wait_loads();               // the loads this wave issued in the last phase 2 have landed
       __syncthreads();
       // ---- phase 2: P_Y(t), S_X(t+1), O += P_X(t) V(t); the loads of K(t+2) and V(t+1) are spread
