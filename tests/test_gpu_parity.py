@@ -84,6 +84,9 @@ def test_every_workgroup_shape(monkeypatch, variant, hq, hkv, d, c, n):
     (32, 8, 128, 512, 300, 512, 512, 0.0),
     (28, 4, 128, 1024, 512, 1024, 512, 0.0),
     (4, 2, 128, 96, 40, 100, 64, 0.25),     # explicit scale, cache below budget going over it
+    (32, 8, 128, 2048, 1024, 2048, 1024, 0.0),   # the bench shape at steady state
+    (2, 2, 64, 6144, 2048, 6144, 2048, 0.0),     # the candidate limit: 8192 per head
+    (4, 1, 64, 37, 5, 40, 8, 0.0),               # a handful of rows, one KV head
 ])
 def test_scores_and_free_selection(hq, hkv, d, c, n, budget, chunk_max, scale):
     """The library's own scores, and the selection it makes from them."""
@@ -220,6 +223,20 @@ def test_odd_sizes_lockstep():
         cache = K.Cache(1, 6, 2, 64, 61, 37, segs, merge=merge, device=DEV)
         U.lockstep_layer(wl, 0, cache, qb, kb, vb, merge)
         cache.close()
+
+
+def test_maximum_candidates_lockstep():
+    """budget + block at the library's limit (8192 candidates per head): the select kernel's
+    eight-candidates-per-thread shape, its largest LDS layout, 2048-row blocks."""
+    segs = (Segment(0, 16 * 16 * 47, 1, 16, 16, 47, 1), Segment(16 * 16 * 47, 256, 0))
+    wl = Workload("max", 1, 2, 2, 64, 2048, 6144, segs, "shared")
+    assert wl.n_tokens == 6 * 2048 and wl.budget + wl.chunk == 8192
+    qb, kb, vb = layer_inputs(wl, 0, seed0=11)
+    cache = K.Cache(1, 2, 2, 64, wl.budget, wl.chunk, segs, merge=True, device=DEV)
+    stats = {}
+    U.lockstep_layer(wl, 0, cache, qb, kb, vb, True, stats=stats)
+    assert stats["merged"] > 0
+    cache.close()
 
 
 def test_budget_at_least_prefix_is_full_attention():
