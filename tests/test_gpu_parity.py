@@ -239,6 +239,25 @@ def test_maximum_candidates_lockstep():
     cache.close()
 
 
+@pytest.mark.parametrize("hq,hkv,d,chunk,budget,segs", [
+    # one slot per head, one token per block: every block evicts exactly one candidate of two
+    (2, 2, 64, 1, 1, (Segment(0, 3 * 3, 1, 3, 3, 1, 0), Segment(9, 4, 0))),
+    # block larger than the budget: the very first block already evicts, with an empty cache
+    (4, 2, 64, 48, 16, (Segment(0, 6 * 8 * 2, 1, 6, 8, 2, 1), Segment(96, 10, 0))),
+    # text only: nothing can merge, merge on must equal merge off
+    (4, 1, 128, 24, 40, (Segment(0, 100, 0),)),
+    # a single-row, single-column grid per plane: only temporal neighbours exist
+    (2, 1, 64, 5, 7, (Segment(0, 23, 1, 1, 1, 23, 1),)),
+])
+def test_degenerate_shapes_lockstep(hq, hkv, d, chunk, budget, segs):
+    wl = Workload("degenerate", 1, hq, hkv, d, chunk, budget, segs, "plane")
+    qb, kb, vb = layer_inputs(wl, 0, seed0=5)
+    for merge in (False, True):
+        cache = K.Cache(1, hq, hkv, d, budget, chunk, segs, merge=merge, device=DEV)
+        U.lockstep_layer(wl, 0, cache, qb, kb, vb, merge)
+        cache.close()
+
+
 def test_budget_at_least_prefix_is_full_attention():
     """Alg. 1 line 8 never fires: the GPU path must equal plain causal attention."""
     wl = get_workload("tiny")
