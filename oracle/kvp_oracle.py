@@ -16,6 +16,8 @@ What follows the paper, and where:
                           Alg. 1 lines 8-11.
   * ``prefill_layer`` / ``LayerCache.step``   the loop of Alg. 1.
   * ``kv_cache_bytes``    Eq. 2 (Sec. 2.2).
+  * ``proxy_scores``      Eq. 4 with the proxy queries of Sec. 3.2 (every
+                          candidate visible to every proxy query).
   * ``keydiff_scores``    the query-agnostic strategy of Sec. 3.2.
 
 Readings where the paper is silent (each is a choice of this build):
@@ -139,6 +141,37 @@ def attend_chunk(q, k_all, v_all, c, scale=None):
         out[:, h, :] = p @ v_all[hk]
         scores[hk] += p.sum(axis=0)
     return out, scores
+
+
+def proxy_scores(q_obs, k_all, scale=None):
+    """Importance of every candidate key under proxy queries (Sec. 3.2 as the
+    paper words it: the observation queries come from the textual prompt, and
+    Eq. 4 is their attention over the keys).  The prompt follows the visual
+    tokens, so a proxy query sees every candidate: no causal mask.
+
+    q_obs  [n_obs, Hq, d]
+    k_all  [Hkv, m, d]   the candidates of each KV head (cache rows, then block rows)
+
+    Returns ``scores [Hkv, m]``: softmax rows of Eq. 4 summed over the proxy
+    queries and over the query heads that share a KV head.
+    """
+    q_obs = np.asarray(q_obs, dtype=np.float64)
+    k_all = np.asarray(k_all, dtype=np.float64)
+    n_obs, hq, d = q_obs.shape
+    hkv, m, _ = k_all.shape
+    assert hq % hkv == 0
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    scores = np.zeros((hkv, m), dtype=np.float64)
+    for h in range(hq):
+        hk = h // g
+        s = scale * (q_obs[:, h, :] @ k_all[hk].T)        # [n_obs, m]
+        s -= s.max(axis=1, keepdims=True)
+        p = np.exp(s)
+        p /= p.sum(axis=1, keepdims=True)
+        scores[hk] += p.sum(axis=0)
+    return scores
 
 
 # ----------------------------------------------------------------------------
@@ -295,6 +328,12 @@ class LayerCache:
         q [n, Hq, d], k, v [n, Hkv, d].  Does not change the cache."""
         _, _, k_all, v_all = self.candidates(t0, k, v)
         return attend_chunk(q, k_all, v_all, self.count, scale)
+
+    def proxy(self, t0, q_obs, k, v, scale=None):
+        """Scores of the candidates of the block starting at ``t0`` under proxy
+        queries ``q_obs [n_obs, Hq, d]``.  Does not change the cache."""
+        _, _, k_all, _ = self.candidates(t0, k, v)
+        return proxy_scores(q_obs, k_all, scale)
 
     def compact(self, t0, k, v, scores32):
         """Append the block and, if over budget, evict (Alg. 1 lines 7-11),

@@ -415,3 +415,54 @@ def test_keydiff_scores_closed_forms():
             nk = math.sqrt(sum(k[h, j, e] ** 2 for e in range(5)))
             nm = math.sqrt(sum(m * m for m in mu))
             assert abs(got[h, j] + dot / (nk * nm)) < 1e-12
+
+
+# ----------------------------------------------------------------------------
+# proxy-query scores (Sec. 3.2, Eq. 4 without a causal mask)
+# ----------------------------------------------------------------------------
+def test_proxy_scores_against_library_softmax_and_loops():
+    from scipy.special import softmax
+    rng = np.random.default_rng(21)
+    n_obs, hq, hkv, m, d = 5, 6, 2, 23, 8
+    q = _rand_bf16(rng, (n_obs, hq, d))
+    k = _rand_bf16(rng, (hkv, m, d))
+    got = O.proxy_scores(q, k)
+    # a library softmax, one head at a time
+    want = np.zeros((hkv, m))
+    for h in range(hq):
+        want[h // (hq // hkv)] += softmax((q[:, h, :] @ k[h // (hq // hkv)].T) / math.sqrt(d), axis=1).sum(axis=0)
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    # plain loops on one query head
+    h, hk = 4, 1
+    col = [0.0] * m
+    for r in range(n_obs):
+        logit = [sum(q[r, h, x] * k[hk, j, x] for x in range(d)) / math.sqrt(d) for j in range(m)]
+        z = sum(math.exp(v) for v in logit)
+        for j in range(m):
+            col[j] += math.exp(logit[j]) / z
+    solo = O.proxy_scores(q[:, h:h + 1, :], k[hk:hk + 1])
+    np.testing.assert_allclose(solo[0], col, rtol=1e-12)
+
+
+def test_proxy_scores_invariants_and_relation_to_block_scores():
+    rng = np.random.default_rng(22)
+    n_obs, hq, hkv, c, n, d = 7, 4, 2, 9, 6, 8
+    q_obs = _rand_bf16(rng, (n_obs, hq, d))
+    k_all = _rand_bf16(rng, (hkv, c + n, d))
+    v_all = _rand_bf16(rng, (hkv, c + n, d))
+    s = O.proxy_scores(q_obs, k_all)
+    # every softmax row sums to one
+    np.testing.assert_allclose(s.sum(axis=1), n_obs * (hq // hkv), rtol=1e-12)
+    # all keys equal: uniform over all candidates, no causal mask
+    ku = np.ones((hkv, c + n, d))
+    np.testing.assert_allclose(O.proxy_scores(q_obs, ku), n_obs * (hq // hkv) / (c + n), rtol=1e-12)
+    # an explicit scale is honoured: scale 0 is uniform whatever the keys
+    np.testing.assert_allclose(O.proxy_scores(q_obs, k_all, scale=0.0), n_obs * (hq // hkv) / (c + n), rtol=1e-12)
+    # the last row of a block sees every candidate, as a proxy query does: the block scores of
+    # a one-row block equal the proxy scores of that row over cache + that row's key
+    q1 = _rand_bf16(rng, (1, hq, d))
+    _, block_scores = O.attend_chunk(q1, k_all[:, :c + 1], v_all[:, :c + 1], c)
+    np.testing.assert_allclose(O.proxy_scores(q1, k_all[:, :c + 1]), block_scores, rtol=1e-12)
+    # permuting the candidates permutes the scores
+    perm = rng.permutation(c + n)
+    np.testing.assert_allclose(O.proxy_scores(q_obs, k_all[:, perm]), s[:, perm], rtol=1e-12)
