@@ -59,18 +59,20 @@ def generate(wl, device, threads):
     return out
 
 
-def run_steps(driver, cache, wl, data, ranges, steps, outs):
+def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None):
     """`steps` whole prefills: every block through every layer, in the order `driver` gives
-    (compactions in line, or on a second stream beside the following layers' attention)."""
+    (compactions in line, or on a second stream beside the following layers' attention).
+    `obs`: per-layer proxy queries that score the candidates instead of the block's own."""
     for _ in range(steps):
         for layer in range(wl.n_layers):
             cache.set_state(layer, 0, 0)
         for t0, n in ranges:
-            driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n])
+            driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n],
+                         (lambda l: obs[l]) if obs is not None else None)
     driver.finish()
 
 
-def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1):
+def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0):
     import torch
     import paper_2604_16734_amd as K
     from kvp_workload import chunk_ranges
@@ -90,7 +92,21 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
     ms_per_step = 1e3 * elapsed / steps
+    proxy = None
+    if n_obs:
+        # the paper's literal scoring (Sec. 3.2): n_obs proxy queries per layer, the same for every block
+        gen = torch.Generator(device=device).manual_seed(1234)
+        obs = [torch.randn((n_obs, wl.n_q_heads, wl.head_dim), generator=gen, device=device).to(torch.bfloat16)
+               for _ in range(wl.n_layers)]
+        run_steps(driver, cache, wl, data, ranges, 1, outs, obs)
+        torch.cuda.synchronize()
+        t_proxy = time.perf_counter()
+        run_steps(driver, cache, wl, data, ranges, steps, outs, obs)
+        torch.cuda.synchronize()
+        t_proxy = (time.perf_counter() - t_proxy) / steps
+        proxy = {"n_obs": n_obs, "tokens_per_s": round(wl.n_tokens / t_proxy, 1), "ms_per_step": round(1e3 * t_proxy, 4)}
     res = {
+        "proxy_scoring": proxy,
         "tokens_per_s": wl.n_tokens / (elapsed / steps),
         "ms_per_step": ms_per_step,
         "persistent_kv_bytes": cache.persistent_bytes,
@@ -188,6 +204,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
                     help="2: kvp_compact of a layer runs on a second stream beside the next layers' kvp_prefill_chunk")
+    ap.add_argument("--n-obs", type=int, default=64,
+                    help="also time the prefill scored with this many proxy queries (0: skip)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -211,7 +229,7 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-    main_res = bench_workload(wl, args.steps, args.warmup, device, threads, streams=args.streams)
+    main_res = bench_workload(wl, args.steps, args.warmup, device, threads, streams=args.streams, n_obs=args.n_obs)
 
     others = {}
     if args.others:
@@ -268,6 +286,7 @@ def main():
             "full_cache_would_be": main_res["full_cache_kv_bytes"],
         },
         "other_workloads": others,
+        "proxy_query_scoring": main_res["proxy_scoring"],
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)

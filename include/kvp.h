@@ -131,6 +131,18 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
 int kvp_prefill_chunk(kvp_cache* cache, int32_t layer, int32_t token_begin, int32_t n_tokens,
                       const void* q, const void* k, const void* v, void* out, void* stream);
 
+/* The same block, scored the way Sec. 3.2 words it: Eq. 4 is taken with proxy
+ * queries from the textual prompt instead of the block's own.
+ *   q_obs [n_obs, n_q_heads, head_dim] bf16, contiguous, device; 1 <= n_obs <= chunk_max
+ * The attention output is that of kvp_prefill_chunk.  A proxy query sees every
+ * candidate (the prompt follows the visual tokens: no causal mask); the scores
+ * are the proxy queries' softmax weights summed over them and over the query
+ * heads that share a KV head.  Other arguments, state changes and errors as for
+ * kvp_prefill_chunk; kvp_compact follows as usual. */
+int kvp_prefill_chunk_proxy(kvp_cache* cache, int32_t layer, int32_t token_begin, int32_t n_tokens,
+                            const void* q, const void* k, const void* v, void* out,
+                            const void* q_obs, int32_t n_obs, void* stream);
+
 /* Alg. 1 lines 7-11 for the block last given to kvp_prefill_chunk(layer).
  * With c cached entries and n block tokens: if c + n <= M all are kept;
  * otherwise each KV head keeps the M candidates with the highest score, equal

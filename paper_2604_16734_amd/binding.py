@@ -83,6 +83,8 @@ def lib():
         L.kvp_init_cache.argtypes = [P(KvpConfig), P(KvpSegment), i32, vp, sz, vp, P(vp)]
         L.kvp_prefill_chunk.restype = ctypes.c_int
         L.kvp_prefill_chunk.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.kvp_prefill_chunk_proxy.restype = ctypes.c_int
+        L.kvp_prefill_chunk_proxy.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
         L.kvp_compact.restype = ctypes.c_int
         L.kvp_compact.argtypes = [vp, i32, vp, vp]
         L.kvp_decode_ready.restype = ctypes.c_int
@@ -139,6 +141,10 @@ def kvp_init_cache(cfg, segs, device_buf, device_bytes, stream=0):
 
 def kvp_prefill_chunk(handle, layer, token_begin, n_tokens, q, k, v, out, stream=0):
     return lib().kvp_prefill_chunk(handle, layer, token_begin, n_tokens, q, k, v, out, stream)
+
+
+def kvp_prefill_chunk_proxy(handle, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, stream=0):
+    return lib().kvp_prefill_chunk_proxy(handle, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, stream)
 
 
 def kvp_compact(handle, layer, scores_override=None, stream=0):
@@ -230,6 +236,21 @@ class Cache:
         rc = kvp_prefill_chunk(self.handle, layer, token_begin, n, self._ptr(q, bf), self._ptr(k, bf),
                                self._ptr(v, bf), self._ptr(out, bf), self._stream(stream))
         _check(rc, "kvp_prefill_chunk")
+        return out
+
+    def prefill_chunk_proxy(self, layer, token_begin, q, k, v, q_obs, out=None, stream=None):
+        bf = self.torch.bfloat16
+        n = q.shape[0]
+        assert q.shape == (n, self.cfg.n_q_heads, self.cfg.head_dim)
+        assert k.shape == v.shape == (n, self.cfg.n_kv_heads, self.cfg.head_dim)
+        assert q_obs.shape[1:] == q.shape[1:]
+        if out is None:
+            out = self.torch.empty_like(q)
+        assert out.shape == q.shape
+        rc = kvp_prefill_chunk_proxy(self.handle, layer, token_begin, n, self._ptr(q, bf), self._ptr(k, bf),
+                                     self._ptr(v, bf), self._ptr(out, bf), self._ptr(q_obs, bf),
+                                     q_obs.shape[0], self._stream(stream))
+        _check(rc, "kvp_prefill_chunk_proxy")
         return out
 
     def compact(self, layer, scores_override=None, stream=None):

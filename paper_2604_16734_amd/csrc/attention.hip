@@ -145,14 +145,14 @@ attention_kernel(const AttnArgs a) {
   const int l32 = lane & 31;
   const int g = lane >> 5;
 
-  const int n = a.n, c = a.c, n_cand = c + n;
+  const int n = a.n, c = a.c, n_cand = c + a.n_keys, shift = a.shift;
   const int row0 = rt * S::kRows;                    // first query row of the workgroup
   const int q0 = row0 + qw * QT * 32;                // first query row of this wave
   const int rows_end = min(n, row0 + S::kRows);
-  const int kv_end = c + rows_end;                   // keys any row of the workgroup can see
+  const int kv_end = min(n_cand, c + rows_end + shift);    // keys any row of the workgroup can see
   const int n_tiles = (kv_end + S::kTk - 1) / S::kTk;
   // tiles [0, n_plain) are visible in full to every row of the workgroup
-  const int n_plain = min(n_tiles, (c + row0 + 1) / S::kTk);
+  const int n_plain = min(n_tiles, (min(c + row0 + shift + 1, n_cand)) / S::kTk);
 
   const u16* kc = a.k_cache + (size_t)hk * a.budget * D;
   const u16* vc = a.v_cache + (size_t)hk * a.budget * D;
@@ -276,7 +276,7 @@ attention_kernel(const AttnArgs a) {
       for (int t = 0; t < QT; ++t) {
         if constexpr (decltype(mask)::value) {
           // key kb + 8 (r / 4) + 4 g + r % 4 is visible when cached, or a block key not after the row
-          const int lim = min(q0 + 32 * t + l32 + c, n_cand - 1) - kb - 4 * g;
+          const int lim = min(q0 + 32 * t + l32 + shift + c, n_cand - 1) - kb - 4 * g;
 #pragma unroll
           for (int r = 0; r < 16; ++r) s[t][r] = (8 * (r >> 2) + (r & 3) <= lim) ? s[t][r] : -INFINITY;
         }
@@ -573,7 +573,7 @@ attention_kernel(const AttnArgs a) {
             const int r = idx / (D / 8), ch = idx % (D / 8);
             const u32x4 val = *reinterpret_cast<const u32x4*>(strip + r * S::kStripRow + 16 * ch);
             const int orow = q0 + 32 * tq + r;
-            if (orow < n)
+            if (orow < n && a.out != nullptr)
               *reinterpret_cast<u32x4*>(a.out + ((size_t)orow * a.n_q_heads + h) * D + 8 * ch) = val;
           }
         }
@@ -611,14 +611,14 @@ attention_kernel(const AttnArgs a) {
       if (!active) continue;
       for (int blk = 0; blk < S::kTk / 32; ++blk) {
         const int kb = t * S::kTk + 32 * blk;
-        if (kb >= n_cand || (kb >= c && kb - c > qs + 31)) continue;    // nothing visible
+        if (kb >= n_cand || (kb >= c && kb - c > qs + 31 + shift)) continue;    // nothing visible
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
         for (int st = 0; st < D / 16; ++st)
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_read_b128(lds_k + 32 * blk * D + k_off[st]), qf[st], s, 0, 0, 0);
-        const int lim = min(qs + l32 + c, n_cand - 1) - kb - 4 * g;
+        const int lim = min(qs + l32 + shift + c, n_cand - 1) - kb - 4 * g;
         float mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -659,16 +659,18 @@ attention_kernel(const AttnArgs a) {
       const int row = qs + l32;
       if (row < n) {
         const float inv = 1.f / l_run;
-        u16* dstp = a.out + ((size_t)row * a.n_q_heads + h) * D + 4 * g;
+        if (a.out != nullptr) {
+          u16* dstp = a.out + ((size_t)row * a.n_q_heads + h) * D + 4 * g;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+          for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            u32x2 pk;
-            pk.x = pack_bf16(o[dt][4 * j] * inv, o[dt][4 * j + 1] * inv);
-            pk.y = pack_bf16(o[dt][4 * j + 2] * inv, o[dt][4 * j + 3] * inv);
-            *reinterpret_cast<u32x2*>(dstp + 32 * dt + 8 * j) = pk;
-          }
+            for (int j = 0; j < 4; ++j) {
+              u32x2 pk;
+              pk.x = pack_bf16(o[dt][4 * j] * inv, o[dt][4 * j + 1] * inv);
+              pk.y = pack_bf16(o[dt][4 * j + 2] * inv, o[dt][4 * j + 3] * inv);
+              *reinterpret_cast<u32x2*>(dstp + 32 * dt + 8 * j) = pk;
+            }
+        }
         if (g == 0) a.lse2[(size_t)h * a.lse_stride + row] = m_run * sl2 + __builtin_log2f(l_run);
       }
     }

@@ -79,14 +79,14 @@ colsum_kernel(const ColsumArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, g = lane >> 5;
-  const int n = a.n, c = a.c, n_cand = c + n;
+  const int n = a.n, c = a.c, n_cand = c + a.n_keys, shift = a.shift;
   const int blk0 = kvb * kBlockKeys;
   const int key0 = blk0 + wave * kWaveKeys;       // first key of this wave
 
   // rows before the block's first key see none of its keys; the tiles from there on are
   // divided evenly among the block's row splits
   const int n_qt = (n + 31) / 32;
-  const int first_tile = blk0 >= c ? (blk0 - c) / 32 : 0;
+  const int first_tile = blk0 - c > shift ? (blk0 - c - shift) / 32 : 0;
   const int visible = n_qt - first_tile;
   const int qt_begin = first_tile + (split * visible) / splits;
   const int qt_end = first_tile + ((split + 1) * visible) / splits;
@@ -202,9 +202,9 @@ colsum_kernel(const ColsumArgs a) {
   // (plain), no key visible to any row (nothing to add), or the causal boundary or the end of
   // the block runs through it (masked)
   auto is_plain = [&](int row0) {
-    return (key0 + kWaveKeys - 1 < c || key0 + kWaveKeys - 1 - c <= row0) && row0 + 32 <= n;
+    return (key0 + kWaveKeys - 1 < c || key0 + kWaveKeys - 1 - c <= row0 + shift) && row0 + 32 <= n;
   };
-  auto is_hidden = [&](int row0) { return key0 - c > row0 + 31; };
+  auto is_hidden = [&](int row0) { return key0 - c > row0 + 31 + shift; };
   auto sum_plain = [&](const f32x16 (&s)[NT], const float (&ls)[16]) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
@@ -213,12 +213,12 @@ colsum_kernel(const ColsumArgs a) {
         colacc[t][r & 1] += __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][r], sl2, -ls[r]));
   };
   auto sum_masked = [&](int row0, const f32x16 (&s)[NT], const float (&ls)[16]) __attribute__((always_inline)) {
-    // row row0 + 4 g + off, off = 8 (r / 4) + r % 4, counts for key kv when kv - c <= row < n:
+    // row row0 + 4 g + off, off = 8 (r / 4) + r % 4, counts for key kv when kv - c - shift <= row < n:
     // first <= off < rows_left, one unsigned comparison (first < rows_left for every real key)
     const int rows_left = n - row0 - 4 * g;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const int first = key0 + 32 * t + l32 - c - row0 - 4 * g;      // negative for a cached key
+      const int first = key0 + 32 * t + l32 - c - shift - row0 - 4 * g;      // negative for a cached key
       const unsigned span = (unsigned)(rows_left - first);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -337,7 +337,7 @@ constexpr int kTargetWorkgroups = 512;     // two per CU, all resident: the laun
 int colsum_max_partials(int /*group*/, int /*chunk_max*/) { return kMaxRowSplits; }
 
 void plan_colsum(ColsumArgs& a, int /*head_dim*/) {
-  const int n_cand = a.c + a.n;
+  const int n_cand = a.c + a.n_keys;
   const int n_qt = (a.n + 31) / 32;
   // 64 keys per wave, or 32 when that is what it takes to spread a small launch over the chip
   int nt = 2;
@@ -356,8 +356,8 @@ void plan_colsum(ColsumArgs& a, int /*head_dim*/) {
     int total = 0, most = 0;
     for (int k = 0; k < a.n_kv_blocks; ++k) {
       const int blk0 = k * block_keys;
-      const int first_tile = blk0 >= a.c ? (blk0 - a.c) / 32 : 0;
-      const int visible = n_qt - first_tile;
+      const int first_tile = blk0 - a.c > a.shift ? (blk0 - a.c - a.shift) / 32 : 0;
+      const int visible = n_qt - first_tile > 0 ? n_qt - first_tile : 1;
       const int splits = (visible + tau - 1) / tau;
       a.split_prefix[k] = total;
       total += splits;

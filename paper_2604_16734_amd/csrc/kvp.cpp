@@ -88,6 +88,7 @@ struct Layer {
   int next_token = 0;
   // the pending block
   int t0 = 0, n = 0;
+  int score_rows = 0, score_shift = 0;   // shape of the scoring pass (for the partial count)
   const u16* k = nullptr;
   const u16* v = nullptr;
   // last block, for kvp_debug_last
@@ -201,7 +202,8 @@ int run_compact(kvp_cache* c, int layer, const float* scores_override, hipStream
   {
     // the partial count of the attention pass that produced the scores
     ColsumArgs tmp{};
-    tmp.n = n; tmp.c = cnt; tmp.n_q_heads = cfg.n_q_heads; tmp.n_kv_heads = cfg.n_kv_heads;
+    tmp.n = L.score_rows; tmp.c = cnt; tmp.n_keys = n; tmp.shift = L.score_shift;
+    tmp.n_q_heads = cfg.n_q_heads; tmp.n_kv_heads = cfg.n_kv_heads;
     plan_colsum(tmp, cfg.head_dim);
     sa.n_partials = tmp.n_partials;
   }
@@ -314,11 +316,17 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
   return KVP_OK;
 }
 
-int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
-                      const void* k, const void* v, void* out, void* stream) {
+namespace {
+
+// kvp_prefill_chunk and kvp_prefill_chunk_proxy: attention for the block; the scoring pass takes
+// its rows from the block's own queries (q_obs null) or from the proxy queries
+int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
+                 const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs, bool proxy,
+                 void* stream) {
   if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
   if (n_tokens < 1 || n_tokens > c->cfg.chunk_max) return KVP_EINVAL;
   if (!c->dry && (!q || !k || !v || !out)) return KVP_EINVAL;
+  if (proxy && (n_obs < 1 || n_obs > c->cfg.chunk_max || (!c->dry && !q_obs))) return KVP_EINVAL;
   Layer& L = c->layers[layer];
   if (L.state != READY) return KVP_ESTATE;
   if (token_begin != L.next_token) return KVP_ESTATE;
@@ -340,6 +348,7 @@ int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t 
   aa.v_cache = c->v_cache(layer);
   aa.lse2 = reinterpret_cast<float*>(set + lay.lse_off);
   aa.n = n_tokens; aa.c = L.count;
+  aa.n_keys = n_tokens; aa.shift = 0;
   aa.n_q_heads = cfg.n_q_heads; aa.n_kv_heads = cfg.n_kv_heads;
   aa.budget = cfg.budget; aa.lse_stride = cfg.chunk_max;
   aa.scale_log2 = c->scale * 1.4426950408889634f;
@@ -347,15 +356,27 @@ int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t 
   int rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
   if (rc) return rc;
 
-  ColsumArgs cs{};
-  cs.q = aa.q; cs.k_new = aa.k_new; cs.k_cache = aa.k_cache; cs.lse2 = aa.lse2;
-  cs.partial = reinterpret_cast<float*>(set + lay.partial_off);
-  cs.n = n_tokens; cs.c = L.count;
-  cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
-  cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
-  cs.scale_log2 = aa.scale_log2;
   // the scores decide an eviction; a block that fits into the cache as it is needs none
   if (L.count + n_tokens > cfg.budget) {
+    if (proxy) {
+      // row statistics of the proxy queries over all candidates (nothing hidden, no output);
+      // they replace the block's own in the scratch set
+      aa.q = static_cast<const u16*>(q_obs);
+      aa.out = nullptr;
+      aa.n = n_obs;
+      aa.shift = n_tokens;
+      plan_attention(aa, cfg.head_dim);
+      rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
+      if (rc) return rc;
+    }
+    ColsumArgs cs{};
+    cs.q = aa.q; cs.k_new = aa.k_new; cs.k_cache = aa.k_cache; cs.lse2 = aa.lse2;
+    cs.partial = reinterpret_cast<float*>(set + lay.partial_off);
+    cs.n = aa.n; cs.c = L.count;
+    cs.n_keys = n_tokens; cs.shift = aa.shift;
+    cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
+    cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
+    cs.scale_log2 = aa.scale_log2;
     plan_colsum(cs, cfg.head_dim);
     rc = launch(c, KVP_K_COLSUM, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
     if (rc) return rc;
@@ -363,11 +384,26 @@ int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t 
 
   L.state = PENDING;
   L.t0 = token_begin; L.n = n_tokens;
+  L.score_rows = proxy ? n_obs : n_tokens;
+  L.score_shift = proxy ? n_tokens : 0;
   L.k = aa.k_new; L.v = aa.v_new;
   L.last_cand = L.count + n_tokens;
   L.has_last = true;
   c->set_owner[set_i] = layer;
   return KVP_OK;
+}
+
+}  // namespace
+
+int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
+                      const void* k, const void* v, void* out, void* stream) {
+  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, nullptr, 0, false, stream);
+}
+
+int kvp_prefill_chunk_proxy(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
+                            const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs,
+                            void* stream) {
+  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, true, stream);
 }
 
 int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void* stream) {

@@ -18,11 +18,13 @@ struct AttnArgs {
   const u16* q;        // [n, Hq, D]
   const u16* k_new;    // [n, Hkv, D]
   const u16* v_new;    // [n, Hkv, D]
-  u16* out;            // [n, Hq, D]
+  u16* out;            // [n, Hq, D], or null: only the row statistics are wanted
   const u16* k_cache;  // this layer: [Hkv, M, D]
   const u16* v_cache;
   float* lse2;         // [Hq, lse_stride]  log2-domain log-sum-exp of every row
   int n, c, n_q_heads, n_kv_heads, budget, lse_stride;
+  int n_keys;          // block keys (k_new, v_new rows); the query rows are n
+  int shift;           // row r sees block key j iff j <= r + shift (0: causal block; >= n_keys: all)
   int n_row_tiles, work_per_xcd, total_work;
   int variant;         // tile shape, chosen by plan_attention
   float scale_log2;    // softmax scale times log2(e)
@@ -38,6 +40,7 @@ struct ColsumArgs {
   const float* lse2;
   float* partial;      // [Hkv, n_partials, cand_stride]
   int n, c, n_q_heads, n_kv_heads, budget, lse_stride, cand_stride;
+  int n_keys, shift;   // as in AttnArgs
   int n_kv_blocks;     // blocks of 256 * subtiles keys
   int n_partials;      // the most row splits any key block has; every key gets that many partials
   int subtiles;        // 32-key subtiles per wave, chosen by plan_colsum

@@ -38,17 +38,23 @@ class Prefill:
             for e in self.compacted:
                 e.record(torch.cuda.current_stream(dev))
 
-    def block(self, t0, qkv_of_layer, out_of_layer=None):
+    def block(self, t0, qkv_of_layer, out_of_layer=None, obs_of_layer=None):
         """One block of the prefix through all layers.  `qkv_of_layer(l)` gives the block's
-        (q, k, v) of layer l, `out_of_layer(l)` the tensor the attention output goes to (or None).
-        Returns the list of outputs."""
+        (q, k, v) of layer l, `out_of_layer(l)` the tensor the attention output goes to (or None),
+        `obs_of_layer(l)` the proxy queries that score the candidates (or None: the block's own
+        queries do).  Returns the list of outputs."""
         cache, torch = self.cache, self.torch
         outs = []
+
+        def attend(layer, q, k, v):
+            out = out_of_layer(layer) if out_of_layer else None
+            if obs_of_layer is not None:
+                return cache.prefill_chunk_proxy(layer, t0, q, k, v, obs_of_layer(layer), out=out)
+            return cache.prefill_chunk(layer, t0, q, k, v, out=out)
         if not self.overlap:
             for layer in range(self.n_layers):
                 q, k, v = qkv_of_layer(layer)
-                outs.append(cache.prefill_chunk(layer, t0, q, k, v,
-                                                out=out_of_layer(layer) if out_of_layer else None))
+                outs.append(attend(layer, q, k, v))
                 cache.compact(layer)
             return outs
         main = torch.cuda.current_stream(cache.device)
@@ -57,8 +63,7 @@ class Prefill:
             main.wait_event(self.compacted[layer])
             if self.n_layers > self.n_sets:
                 main.wait_event(self.compacted[(layer - self.n_sets) % self.n_layers])
-            outs.append(cache.prefill_chunk(layer, t0, q, k, v,
-                                            out=out_of_layer(layer) if out_of_layer else None))
+            outs.append(attend(layer, q, k, v))
             self.attended[layer].record(main)
             self.side.wait_event(self.attended[layer])
             cache.compact(layer, stream=self.side)

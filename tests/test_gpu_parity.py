@@ -24,8 +24,9 @@ def _rand_bits(rng, shape, scale=1.0):
     return f32_to_bf16_bits((scale * rng.standard_normal(shape)).astype(np.float32))
 
 
-def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0):
-    """One prefill_chunk on a cache preloaded with c random entries."""
+def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0, n_obs=0):
+    """One prefill_chunk (or prefill_chunk_proxy with n_obs proxy queries) on a cache preloaded
+    with c random entries."""
     rng = np.random.default_rng(seed)
     segs = [Segment(0, 100000, 0)]
     cache = K.Cache(1, hq, hkv, d, budget, chunk_max, segs, merge=False, softmax_scale=scale, device=DEV)
@@ -40,9 +41,15 @@ def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0):
     U.upload_state(cache, 0, oc)
     cache.set_state(0, c, c)
     qb, kb, vb = _rand_bits(rng, (n, hq, d)), _rand_bits(rng, (n, hkv, d)), _rand_bits(rng, (n, hkv, d))
-    out = cache.prefill_chunk(0, c, U.bits_to_torch(qb), U.bits_to_torch(kb), U.bits_to_torch(vb))
     q64, k64, v64 = (O.bf16_bits_to_f64(x) for x in (qb, kb, vb))
     out_ref, scores_ref = oc.attend(c, q64, k64, v64, scale or None)
+    if n_obs:
+        ob = _rand_bits(rng, (n_obs, hq, d))
+        out = cache.prefill_chunk_proxy(0, c, U.bits_to_torch(qb), U.bits_to_torch(kb), U.bits_to_torch(vb),
+                                        U.bits_to_torch(ob))
+        scores_ref = oc.proxy(c, O.bf16_bits_to_f64(ob), k64, v64, scale or None)
+    else:
+        out = cache.prefill_chunk(0, c, U.bits_to_torch(qb), U.bits_to_torch(kb), U.bits_to_torch(vb))
     err = U.out_rel_err(U.torch_bf16_to_f64(out), out_ref)
     # finish the scores the way the library does: compact with its own scores, then read them
     cache.compact(0)
@@ -109,6 +116,33 @@ def test_scores_and_free_selection(hq, hkv, d, c, n, budget, chunk_max, scale):
     idx = idx.cpu().numpy()
     for hk in range(hkv):
         assert sorted(idx[hk].tolist()) == sorted(tok[hk][keep[hk]].tolist())
+    cache.close()
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,n,budget,chunk_max,n_obs,scale", [
+    (4, 4, 64, 128, 64, 128, 64, 16, 0.0),
+    (8, 2, 128, 200, 150, 200, 256, 33, 0.0),         # ragged proxy rows
+    (4, 2, 128, 96, 40, 100, 64, 1, 0.25),            # a single proxy query, explicit scale
+    (28, 4, 128, 1024, 512, 1024, 512, 512, 0.0),     # as many proxy queries as a block holds
+    (32, 8, 128, 2048, 1024, 2048, 1024, 64, 0.0),    # the bench shape with a 64-token prompt
+    (2, 2, 64, 6144, 2048, 6144, 2048, 100, 0.0),     # the candidate limit
+    (4, 2, 64, 0, 96, 32, 96, 8, 0.0),                # empty cache, block larger than the budget
+])
+def test_proxy_query_scores_and_selection(hq, hkv, d, c, n, budget, chunk_max, n_obs, scale):
+    """Scores taken with proxy queries (every candidate visible to each of them), the attention
+    output unchanged, and the selection made from those scores."""
+    cache, oc, err, scores_ref, _ = _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed=3 * c + n + n_obs,
+                                                    scale=scale, n_obs=n_obs)
+    assert err <= U.OUT_TOL, err
+    scores_gpu, keep, dst = cache.debug_last(0)
+    scores_gpu = scores_gpu.cpu().numpy()
+    g = hq // hkv
+    U.check_scores(scores_gpu, scores_ref, n_obs * g)
+    np.testing.assert_allclose(scores_gpu.sum(axis=1), n_obs * g, rtol=1e-4)
+    tok = np.concatenate([oc.idx, np.broadcast_to(np.arange(c, c + n), (hkv, n))], axis=1)
+    keep = keep.cpu().numpy().astype(bool)
+    for hk in range(hkv):
+        assert np.array_equal(keep[hk], O.select_keep(scores_gpu[hk], tok[hk], budget))
     cache.close()
 
 

@@ -133,6 +133,27 @@ def test_state_machine_and_counts():
         K.kvp_free_cache(h)
 
 
+def test_proxy_entry_point_follows_the_same_state_machine():
+    wl = get_workload("tiny")
+    cfg = _cfg(wl)
+    rc, h = K.kvp_init_cache(cfg, wl.segments, None, 0)
+    assert rc == K.KVP_OK and h
+    try:
+        assert K.kvp_prefill_chunk_proxy(h, 0, 0, 8, 0, 0, 0, 0, 0, 0) == K.KVP_EINVAL            # no proxy rows
+        assert K.kvp_prefill_chunk_proxy(h, 0, 0, 8, 0, 0, 0, 0, 0, wl.chunk + 1) == K.KVP_EINVAL  # too many
+        assert K.kvp_prefill_chunk_proxy(h, 0, 3, 8, 0, 0, 0, 0, 0, 4) == K.KVP_ESTATE            # tokens skipped
+        count = 0
+        for t0, n in chunk_ranges(wl.n_tokens, wl.chunk):
+            assert K.kvp_prefill_chunk_proxy(h, 0, t0, n, 0, 0, 0, 0, 0, 4) == K.KVP_OK
+            assert K.kvp_prefill_chunk(h, 0, t0 + n, 1, 0, 0, 0, 0) == K.KVP_ESTATE               # pending
+            assert K.kvp_compact(h, 0) == K.KVP_OK
+            count = min(wl.budget, count + n)
+            rc, vw = K.kvp_decode_ready(h, 0)
+            assert rc == K.KVP_OK and vw.count == count and vw.next_token == t0 + n
+    finally:
+        K.kvp_free_cache(h)
+
+
 def test_scratch_sets_gate_pending_layers():
     wl = get_workload("single_image")
     for sets, second_ok in ((1, False), (2, True)):
