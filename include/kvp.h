@@ -188,7 +188,7 @@ int kvp_debug_last(kvp_cache* cache, int32_t layer, const float** scores, const 
  * recorded events, adds them up per kernel kind and clears them. */
 enum {
   KVP_K_ATTENTION = 0, KVP_K_COLSUM = 1, KVP_K_SELECT = 2, KVP_K_MERGE = 3,
-  KVP_K_MOVE = 4, KVP_K_COUNT = 5
+  KVP_K_MOVE = 4, KVP_K_ROWSTAT = 5, KVP_K_COUNT = 6
 };
 typedef struct kvp_kernel_stat {
   int64_t launches;

@@ -16,7 +16,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "kvp.h")
 KVP_OK, KVP_EINVAL, KVP_ESTATE, KVP_ENOMEM, KVP_EDEVICE = 0, -1, -2, -3, -4
 KVP_TEXT, KVP_VISUAL = 0, 1
 KVP_FLAG_DRY_RUN = 1
-KERNEL_KINDS = ("attention", "colsum", "select", "merge", "move")
+KERNEL_KINDS = ("attention", "colsum", "select", "merge", "move", "rowstat")
 
 
 class KvpError(RuntimeError):

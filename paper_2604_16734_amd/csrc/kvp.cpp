@@ -252,6 +252,7 @@ const char* kvp_kernel_name(int32_t kind) {
     case KVP_K_SELECT: return "select";
     case KVP_K_MERGE: return "merge";
     case KVP_K_MOVE: return "move";
+    case KVP_K_ROWSTAT: return "rowstat";
     default: return "?";
   }
 }
@@ -365,8 +366,26 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
       aa.out = nullptr;
       aa.n = n_obs;
       aa.shift = n_tokens;
-      plan_attention(aa, cfg.head_dim);
-      rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
+      // a short list of proxy queries would leave the attention kernel with a handful of
+      // workgroups: spread the keys instead.  The per-block partials borrow the memory of the
+      // column-sum partials, which the scoring pass only writes afterwards.
+      const int n_kb = rowstat_key_blocks(L.count + n_tokens);
+      const size_t need = (size_t)cfg.n_q_heads * n_obs * n_kb * 2 * sizeof(float);
+      const size_t have = (size_t)cfg.n_kv_heads * lay.max_partials * lay.cand_stride * sizeof(float);
+      if ((long long)n_obs * cfg.n_q_heads < 128 * 64 && need <= have) {
+        RowstatArgs ra{};
+        ra.q = aa.q; ra.k_new = aa.k_new; ra.k_cache = aa.k_cache; ra.lse2 = aa.lse2;
+        ra.part_m = reinterpret_cast<float*>(set + lay.partial_off);
+        ra.part_l = ra.part_m + (size_t)cfg.n_q_heads * n_obs * n_kb;
+        ra.n = n_obs; ra.c = L.count; ra.n_keys = n_tokens;
+        ra.n_q_heads = cfg.n_q_heads; ra.n_kv_heads = cfg.n_kv_heads;
+        ra.budget = cfg.budget; ra.lse_stride = cfg.chunk_max;
+        ra.scale_log2 = aa.scale_log2;
+        rc = launch(c, KVP_K_ROWSTAT, s, [&] { return launch_rowstat(ra, cfg.head_dim, s); });
+      } else {
+        plan_attention(aa, cfg.head_dim);
+        rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
+      }
       if (rc) return rc;
     }
     ColsumArgs cs{};

@@ -52,6 +52,21 @@ struct ColsumArgs {
   int split_prefix[kColsumMaxKvBlocks + 1];
 };
 
+// Row statistics of a short list of proxy queries over all candidates (rowstat.hip).
+struct RowstatArgs {
+  const u16* q;        // [n, Hq, D] proxy queries
+  const u16* k_new;    // [n_keys, Hkv, D]
+  const u16* k_cache;  // this layer: [Hkv, M, D]
+  float* lse2;         // [Hq, lse_stride] out
+  float* part_m;       // [Hq, n, n_kv_blocks] scratch: row maximum per key block (raw logits)
+  float* part_l;       // [Hq, n, n_kv_blocks] scratch: sum of exp2 against that maximum
+  int n, c, n_keys, n_q_heads, n_kv_heads, budget, lse_stride;
+  int n_kv_blocks;     // set by launch_rowstat
+  float scale_log2;
+};
+int rowstat_key_blocks(int n_cand);
+hipError_t launch_rowstat(RowstatArgs a, int head_dim, hipStream_t s);
+
 // Device copy of one prefix segment.
 struct Seg {
   int begin, n, kind, gh, gw, planes, temporal;

@@ -30,7 +30,7 @@ def test_strerror_and_kernel_names():
     assert K.kvp_strerror(0) == "ok"
     for code in (-1, -2, -3, -4, -99):
         assert K.kvp_strerror(code)
-    assert [K.kvp_kernel_name(i) for i in range(5)] == list(K.KERNEL_KINDS)
+    assert [K.kvp_kernel_name(i) for i in range(len(K.KERNEL_KINDS))] == list(K.KERNEL_KINDS)
 
 
 def test_persistent_bytes_follow_eq2():
