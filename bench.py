@@ -59,16 +59,17 @@ def generate(wl, device, threads):
     return out
 
 
-def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None):
+def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None, keydiff=False):
     """`steps` whole prefills: every block through every layer, in the order `driver` gives
     (compactions in line, or on a second stream beside the following layers' attention).
-    `obs`: per-layer proxy queries that score the candidates instead of the block's own."""
+    `obs`: per-layer proxy queries that score the candidates instead of the block's own;
+    `keydiff`: the keys alone score them."""
     for _ in range(steps):
         for layer in range(wl.n_layers):
             cache.set_state(layer, 0, 0)
         for t0, n in ranges:
             driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n],
-                         (lambda l: obs[l]) if obs is not None else None)
+                         (lambda l: obs[l]) if obs is not None else None, keydiff)
     driver.finish()
 
 
@@ -105,7 +106,14 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         torch.cuda.synchronize()
         t_proxy = (time.perf_counter() - t_proxy) / steps
         proxy = {"n_obs": n_obs, "tokens_per_s": round(wl.n_tokens / t_proxy, 1), "ms_per_step": round(1e3 * t_proxy, 4)}
+    run_steps(driver, cache, wl, data, ranges, 1, outs, keydiff=True)
+    torch.cuda.synchronize()
+    t_kd = time.perf_counter()
+    run_steps(driver, cache, wl, data, ranges, steps, outs, keydiff=True)
+    torch.cuda.synchronize()
+    t_kd = (time.perf_counter() - t_kd) / steps
     res = {
+        "keydiff_scoring": {"tokens_per_s": round(wl.n_tokens / t_kd, 1), "ms_per_step": round(1e3 * t_kd, 4)},
         "proxy_scoring": proxy,
         "tokens_per_s": wl.n_tokens / (elapsed / steps),
         "ms_per_step": ms_per_step,
@@ -287,6 +295,7 @@ def main():
         },
         "other_workloads": others,
         "proxy_query_scoring": main_res["proxy_scoring"],
+        "keydiff_scoring": main_res["keydiff_scoring"],
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)

@@ -143,6 +143,15 @@ int kvp_prefill_chunk_proxy(kvp_cache* cache, int32_t layer, int32_t token_begin
                             const void* q, const void* k, const void* v, void* out,
                             const void* q_obs, int32_t n_obs, void* stream);
 
+/* The same block, scored without any query (the query-agnostic strategy of
+ * Sec. 3.2): the anchor is the mean of the candidate keys of a KV head (cache
+ * entries and block keys alike), and a key's score is minus its cosine
+ * similarity to the anchor, so that the keys that deviate most are kept.
+ * The attention output is that of kvp_prefill_chunk; arguments, state changes
+ * and errors likewise. */
+int kvp_prefill_chunk_keydiff(kvp_cache* cache, int32_t layer, int32_t token_begin, int32_t n_tokens,
+                              const void* q, const void* k, const void* v, void* out, void* stream);
+
 /* Alg. 1 lines 7-11 for the block last given to kvp_prefill_chunk(layer).
  * With c cached entries and n block tokens: if c + n <= M all are kept;
  * otherwise each KV head keeps the M candidates with the highest score, equal
@@ -188,7 +197,7 @@ int kvp_debug_last(kvp_cache* cache, int32_t layer, const float** scores, const 
  * recorded events, adds them up per kernel kind and clears them. */
 enum {
   KVP_K_ATTENTION = 0, KVP_K_COLSUM = 1, KVP_K_SELECT = 2, KVP_K_MERGE = 3,
-  KVP_K_MOVE = 4, KVP_K_ROWSTAT = 5, KVP_K_COUNT = 6
+  KVP_K_MOVE = 4, KVP_K_ROWSTAT = 5, KVP_K_KEYDIFF = 6, KVP_K_COUNT = 7
 };
 typedef struct kvp_kernel_stat {
   int64_t launches;

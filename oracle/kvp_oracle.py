@@ -335,6 +335,12 @@ class LayerCache:
         _, _, k_all, _ = self.candidates(t0, k, v)
         return proxy_scores(q_obs, k_all, scale)
 
+    def keydiff(self, t0, k, v):
+        """Query-agnostic scores of the candidates of the block starting at
+        ``t0``.  Does not change the cache."""
+        _, _, k_all, _ = self.candidates(t0, k, v)
+        return keydiff_scores(k_all)
+
     def compact(self, t0, k, v, scores32):
         """Append the block and, if over budget, evict (Alg. 1 lines 7-11),
         merging evicted visual tokens when ``merge`` is on.

@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     KVP_FLAG_DRY_RUN, KERNEL_KINDS, KvpError, KvpConfig, KvpSegment, KvpView, KvpKernelStat,
     lib, library_path, declared_symbols,
     kvp_strerror, kvp_cache_bytes, kvp_persistent_bytes, kvp_init_cache, kvp_prefill_chunk,
-    kvp_prefill_chunk_proxy,
+    kvp_prefill_chunk_proxy, kvp_prefill_chunk_keydiff,
     kvp_compact, kvp_decode_ready, kvp_set_state, kvp_debug_last, kvp_profile_enable,
     kvp_profile_read, kvp_kernel_name, kvp_free_cache,
     Cache,

@@ -16,7 +16,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "kvp.h")
 KVP_OK, KVP_EINVAL, KVP_ESTATE, KVP_ENOMEM, KVP_EDEVICE = 0, -1, -2, -3, -4
 KVP_TEXT, KVP_VISUAL = 0, 1
 KVP_FLAG_DRY_RUN = 1
-KERNEL_KINDS = ("attention", "colsum", "select", "merge", "move", "rowstat")
+KERNEL_KINDS = ("attention", "colsum", "select", "merge", "move", "rowstat", "keydiff")
 
 
 class KvpError(RuntimeError):
@@ -85,6 +85,8 @@ def lib():
         L.kvp_prefill_chunk.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.kvp_prefill_chunk_proxy.restype = ctypes.c_int
         L.kvp_prefill_chunk_proxy.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
+        L.kvp_prefill_chunk_keydiff.restype = ctypes.c_int
+        L.kvp_prefill_chunk_keydiff.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.kvp_compact.restype = ctypes.c_int
         L.kvp_compact.argtypes = [vp, i32, vp, vp]
         L.kvp_decode_ready.restype = ctypes.c_int
@@ -145,6 +147,10 @@ def kvp_prefill_chunk(handle, layer, token_begin, n_tokens, q, k, v, out, stream
 
 def kvp_prefill_chunk_proxy(handle, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, stream=0):
     return lib().kvp_prefill_chunk_proxy(handle, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, stream)
+
+
+def kvp_prefill_chunk_keydiff(handle, layer, token_begin, n_tokens, q, k, v, out, stream=0):
+    return lib().kvp_prefill_chunk_keydiff(handle, layer, token_begin, n_tokens, q, k, v, out, stream)
 
 
 def kvp_compact(handle, layer, scores_override=None, stream=0):
@@ -236,6 +242,19 @@ class Cache:
         rc = kvp_prefill_chunk(self.handle, layer, token_begin, n, self._ptr(q, bf), self._ptr(k, bf),
                                self._ptr(v, bf), self._ptr(out, bf), self._stream(stream))
         _check(rc, "kvp_prefill_chunk")
+        return out
+
+    def prefill_chunk_keydiff(self, layer, token_begin, q, k, v, out=None, stream=None):
+        bf = self.torch.bfloat16
+        n = q.shape[0]
+        assert q.shape == (n, self.cfg.n_q_heads, self.cfg.head_dim)
+        assert k.shape == v.shape == (n, self.cfg.n_kv_heads, self.cfg.head_dim)
+        if out is None:
+            out = self.torch.empty_like(q)
+        assert out.shape == q.shape
+        rc = kvp_prefill_chunk_keydiff(self.handle, layer, token_begin, n, self._ptr(q, bf), self._ptr(k, bf),
+                                       self._ptr(v, bf), self._ptr(out, bf), self._stream(stream))
+        _check(rc, "kvp_prefill_chunk_keydiff")
         return out
 
     def prefill_chunk_proxy(self, layer, token_begin, q, k, v, q_obs, out=None, stream=None):

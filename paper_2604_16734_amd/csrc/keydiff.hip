@@ -1,0 +1,118 @@
+// Query-agnostic importance (the KeyDiff-style strategy of Sec. 3.2): the anchor
+// is the mean of the candidate keys of a KV head, and a key scores the higher
+// the less it resembles the anchor: score_j = -cos(k_j, mu).
+//
+// Pure streaming work, bound by HBM (every candidate key is read twice, the
+// second time from L2): two small kernels.
+//   keydiff_sum_kernel    column sums of the keys of one slice of one head
+//                         (fp32, rows added in ascending order by each lane,
+//                         slices folded in ascending order afterwards)
+//   keydiff_score_kernel  folds the slices into mu, then four lanes per key:
+//                         dot(k, mu) and |k|^2 over a quarter of the channels
+//                         each, added across the four lanes
+// The scores go where the scoring pass of the query-aware strategy leaves its
+// single partial, so the selection that follows is the same.
+#include "kvp_internal.h"
+
+namespace kvp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSliceKeys = 64;         // keys per workgroup of the sum kernel
+
+__device__ __forceinline__ float bf16_at(const u16* p) { return __uint_as_float((unsigned)*p << 16); }
+
+__device__ __forceinline__ const u16* key_row(const KeydiffArgs& a, int hk, int kv, int D) {
+  return kv < a.c ? a.k_cache + ((size_t)hk * a.budget + kv) * D
+                  : a.k_new + ((size_t)(kv - a.c) * a.n_kv_heads + hk) * D;
+}
+
+// grid (slices, Hkv); thread t: channel t % D, row residue t / D
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+keydiff_sum_kernel(const KeydiffArgs a) {
+  constexpr int kLanesPerRow = D, kRowsAtOnce = kThreads / D;
+  __shared__ float s_part[kRowsAtOnce][D];
+  const int slice = blockIdx.x, hk = blockIdx.y;
+  const int ch = threadIdx.x % kLanesPerRow, rr = threadIdx.x / kLanesPerRow;
+  const int n_cand = a.c + a.n_keys;
+  const int k0 = slice * kSliceKeys, k1 = min(n_cand, k0 + kSliceKeys);
+  float acc = 0.f;
+  for (int kv = k0 + rr; kv < k1; kv += kRowsAtOnce) acc += bf16_at(key_row(a, hk, kv, D) + ch);
+  s_part[rr][ch] = acc;
+  __syncthreads();
+  if (rr == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < kRowsAtOnce; ++r) t += s_part[r][ch];
+    a.sums[((size_t)hk * a.n_slices + slice) * D + ch] = t;
+  }
+}
+
+// grid (blocks of 64 keys, Hkv); four lanes per key, 16 keys per wave
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+keydiff_score_kernel(const KeydiffArgs a) {
+  __shared__ __align__(16) float s_mu[D];
+  __shared__ float s_mu2;
+  const int hk = blockIdx.y;
+  const int n_cand = a.c + a.n_keys;
+  if (threadIdx.x < D) {
+    float t = 0.f;
+    for (int s = 0; s < a.n_slices; ++s) t += a.sums[((size_t)hk * a.n_slices + s) * D + threadIdx.x];
+    s_mu[threadIdx.x] = t / (float)n_cand;
+  }
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float m2 = 0.f;
+    for (int i = threadIdx.x; i < D; i += 64) m2 += s_mu[i] * s_mu[i];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) m2 += __shfl_xor(m2, off, 64);
+    if (threadIdx.x == 0) s_mu2 = m2;
+  }
+  __syncthreads();
+  constexpr int kPer = D / 4;                      // channels per lane: a quarter of a key
+  const int kv = blockIdx.x * a.keys_per_block + (threadIdx.x >> 2);
+  const int quarter = threadIdx.x & 3;
+  float dot = 0.f, k2 = 0.f;
+  if (kv < n_cand) {
+    const u16* row = key_row(a, hk, kv, D) + kPer * quarter;
+#pragma unroll
+    for (int i = 0; i < kPer; i += 8) {
+      const uint4 w = *reinterpret_cast<const uint4*>(row + i);
+      const unsigned ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float lo = __uint_as_float(ws[j] << 16), hi = __uint_as_float(ws[j] & 0xFFFF0000u);
+        const float m0 = s_mu[kPer * quarter + i + 2 * j], m1 = s_mu[kPer * quarter + i + 2 * j + 1];
+        dot = __builtin_fmaf(lo, m0, dot); dot = __builtin_fmaf(hi, m1, dot);
+        k2 = __builtin_fmaf(lo, lo, k2); k2 = __builtin_fmaf(hi, hi, k2);
+      }
+    }
+  }
+  dot += __shfl_xor(dot, 1, 64); k2 += __shfl_xor(k2, 1, 64);
+  dot += __shfl_xor(dot, 2, 64); k2 += __shfl_xor(k2, 2, 64);
+  if (quarter == 0 && kv < n_cand)
+    a.scores[(size_t)hk * a.cand_stride + kv] = -dot / (sqrtf(k2) * sqrtf(s_mu2));
+}
+
+}  // namespace
+
+int keydiff_slices(int n_cand) { return (n_cand + kSliceKeys - 1) / kSliceKeys; }
+
+hipError_t launch_keydiff(KeydiffArgs a, int head_dim, hipStream_t s) {
+  const int n_cand = a.c + a.n_keys;
+  a.n_slices = keydiff_slices(n_cand);
+  a.keys_per_block = 64;
+  const dim3 g1(a.n_slices, a.n_kv_heads), g2((n_cand + a.keys_per_block - 1) / a.keys_per_block, a.n_kv_heads);
+  if (head_dim == 128) {
+    hipLaunchKernelGGL(keydiff_sum_kernel<128>, g1, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(keydiff_score_kernel<128>, g2, dim3(kThreads), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(keydiff_sum_kernel<64>, g1, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(keydiff_score_kernel<64>, g2, dim3(kThreads), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace kvp

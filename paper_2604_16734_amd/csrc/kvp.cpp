@@ -88,7 +88,7 @@ struct Layer {
   int next_token = 0;
   // the pending block
   int t0 = 0, n = 0;
-  int score_rows = 0, score_shift = 0;   // shape of the scoring pass (for the partial count)
+  int n_partials = 0;   // partial score arrays the scoring pass of the pending block left
   const u16* k = nullptr;
   const u16* v = nullptr;
   // last block, for kvp_debug_last
@@ -199,14 +199,7 @@ int run_compact(kvp_cache* c, int layer, const float* scores_override, hipStream
   sa.n_segs = (int)c->segs.size();
   sa.c = cnt; sa.n = n; sa.t0 = L.t0; sa.budget = M;
   sa.cand_stride = lay.cand_stride; sa.chunk_max = cfg.chunk_max;
-  {
-    // the partial count of the attention pass that produced the scores
-    ColsumArgs tmp{};
-    tmp.n = L.score_rows; tmp.c = cnt; tmp.n_keys = n; tmp.shift = L.score_shift;
-    tmp.n_q_heads = cfg.n_q_heads; tmp.n_kv_heads = cfg.n_kv_heads;
-    plan_colsum(tmp, cfg.head_dim);
-    sa.n_partials = tmp.n_partials;
-  }
+  sa.n_partials = L.n_partials;
   sa.merge = cfg.merge;
   sa.items = (cnt + n + 1023) / 1024;
   int ts = 2;
@@ -253,6 +246,7 @@ const char* kvp_kernel_name(int32_t kind) {
     case KVP_K_MERGE: return "merge";
     case KVP_K_MOVE: return "move";
     case KVP_K_ROWSTAT: return "rowstat";
+    case KVP_K_KEYDIFF: return "keydiff";
     default: return "?";
   }
 }
@@ -319,11 +313,14 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
 
 namespace {
 
-// kvp_prefill_chunk and kvp_prefill_chunk_proxy: attention for the block; the scoring pass takes
-// its rows from the block's own queries (q_obs null) or from the proxy queries
+enum { kScoreOwn = 0, kScoreProxy = 1, kScoreKeydiff = 2 };
+
+// kvp_prefill_chunk and its variants: attention for the block; the scores come from the block's
+// own queries, from proxy queries, or from the keys alone
 int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
-                 const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs, bool proxy,
+                 const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs, int mode,
                  void* stream) {
+  const bool proxy = mode == kScoreProxy;
   if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
   if (n_tokens < 1 || n_tokens > c->cfg.chunk_max) return KVP_EINVAL;
   if (!c->dry && (!q || !k || !v || !out)) return KVP_EINVAL;
@@ -388,23 +385,34 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
       }
       if (rc) return rc;
     }
-    ColsumArgs cs{};
-    cs.q = aa.q; cs.k_new = aa.k_new; cs.k_cache = aa.k_cache; cs.lse2 = aa.lse2;
-    cs.partial = reinterpret_cast<float*>(set + lay.partial_off);
-    cs.n = aa.n; cs.c = L.count;
-    cs.n_keys = n_tokens; cs.shift = aa.shift;
-    cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
-    cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
-    cs.scale_log2 = aa.scale_log2;
-    plan_colsum(cs, cfg.head_dim);
-    rc = launch(c, KVP_K_COLSUM, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
-    if (rc) return rc;
+    if (mode == kScoreKeydiff) {
+      KeydiffArgs ka{};
+      ka.k_new = aa.k_new; ka.k_cache = aa.k_cache;
+      ka.scores = reinterpret_cast<float*>(set + lay.partial_off);          // the one "partial"
+      ka.sums = ka.scores + (size_t)cfg.n_kv_heads * lay.cand_stride;
+      ka.c = L.count; ka.n_keys = n_tokens; ka.n_kv_heads = cfg.n_kv_heads;
+      ka.budget = cfg.budget; ka.cand_stride = lay.cand_stride;
+      rc = launch(c, KVP_K_KEYDIFF, s, [&] { return launch_keydiff(ka, cfg.head_dim, s); });
+      if (rc) return rc;
+      L.n_partials = 1;
+    } else {
+      ColsumArgs cs{};
+      cs.q = aa.q; cs.k_new = aa.k_new; cs.k_cache = aa.k_cache; cs.lse2 = aa.lse2;
+      cs.partial = reinterpret_cast<float*>(set + lay.partial_off);
+      cs.n = aa.n; cs.c = L.count;
+      cs.n_keys = n_tokens; cs.shift = aa.shift;
+      cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
+      cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
+      cs.scale_log2 = aa.scale_log2;
+      plan_colsum(cs, cfg.head_dim);
+      rc = launch(c, KVP_K_COLSUM, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
+      if (rc) return rc;
+      L.n_partials = cs.n_partials;
+    }
   }
 
   L.state = PENDING;
   L.t0 = token_begin; L.n = n_tokens;
-  L.score_rows = proxy ? n_obs : n_tokens;
-  L.score_shift = proxy ? n_tokens : 0;
   L.k = aa.k_new; L.v = aa.v_new;
   L.last_cand = L.count + n_tokens;
   L.has_last = true;
@@ -416,13 +424,18 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
 
 int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
                       const void* k, const void* v, void* out, void* stream) {
-  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, nullptr, 0, false, stream);
+  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, nullptr, 0, kScoreOwn, stream);
 }
 
 int kvp_prefill_chunk_proxy(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
                             const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs,
                             void* stream) {
-  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, true, stream);
+  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, kScoreProxy, stream);
+}
+
+int kvp_prefill_chunk_keydiff(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
+                              const void* k, const void* v, void* out, void* stream) {
+  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, nullptr, 0, kScoreKeydiff, stream);
 }
 
 int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void* stream) {

@@ -67,6 +67,18 @@ struct RowstatArgs {
 int rowstat_key_blocks(int n_cand);
 hipError_t launch_rowstat(RowstatArgs a, int head_dim, hipStream_t s);
 
+// Query-agnostic scores of all candidates (keydiff.hip).
+struct KeydiffArgs {
+  const u16* k_new;    // [n_keys, Hkv, D]
+  const u16* k_cache;  // this layer: [Hkv, M, D]
+  float* sums;         // [Hkv, n_slices, D] scratch: column sums of the keys, one per slice
+  float* scores;       // [Hkv, cand_stride] out
+  int c, n_keys, n_kv_heads, budget, cand_stride;
+  int n_slices, keys_per_block;   // set by launch_keydiff
+};
+int keydiff_slices(int n_cand);
+hipError_t launch_keydiff(KeydiffArgs a, int head_dim, hipStream_t s);
+
 // Device copy of one prefix segment.
 struct Seg {
   int begin, n, kind, gh, gw, planes, temporal;

@@ -38,16 +38,18 @@ class Prefill:
             for e in self.compacted:
                 e.record(torch.cuda.current_stream(dev))
 
-    def block(self, t0, qkv_of_layer, out_of_layer=None, obs_of_layer=None):
+    def block(self, t0, qkv_of_layer, out_of_layer=None, obs_of_layer=None, keydiff=False):
         """One block of the prefix through all layers.  `qkv_of_layer(l)` gives the block's
-        (q, k, v) of layer l, `out_of_layer(l)` the tensor the attention output goes to (or None),
-        `obs_of_layer(l)` the proxy queries that score the candidates (or None: the block's own
-        queries do).  Returns the list of outputs."""
+        (q, k, v) of layer l, `out_of_layer(l)` the tensor the attention output goes to (or None).
+        The candidates are scored by the block's own queries, or by the proxy queries
+        `obs_of_layer(l)`, or (`keydiff`) by the keys alone.  Returns the list of outputs."""
         cache, torch = self.cache, self.torch
         outs = []
 
         def attend(layer, q, k, v):
             out = out_of_layer(layer) if out_of_layer else None
+            if keydiff:
+                return cache.prefill_chunk_keydiff(layer, t0, q, k, v, out=out)
             if obs_of_layer is not None:
                 return cache.prefill_chunk_proxy(layer, t0, q, k, v, obs_of_layer(layer), out=out)
             return cache.prefill_chunk(layer, t0, q, k, v, out=out)

@@ -24,7 +24,7 @@ def _rand_bits(rng, shape, scale=1.0):
     return f32_to_bf16_bits((scale * rng.standard_normal(shape)).astype(np.float32))
 
 
-def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0, n_obs=0):
+def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0, n_obs=0, keydiff=False):
     """One prefill_chunk (or prefill_chunk_proxy with n_obs proxy queries) on a cache preloaded
     with c random entries."""
     rng = np.random.default_rng(seed)
@@ -43,7 +43,10 @@ def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0, n_obs=
     qb, kb, vb = _rand_bits(rng, (n, hq, d)), _rand_bits(rng, (n, hkv, d)), _rand_bits(rng, (n, hkv, d))
     q64, k64, v64 = (O.bf16_bits_to_f64(x) for x in (qb, kb, vb))
     out_ref, scores_ref = oc.attend(c, q64, k64, v64, scale or None)
-    if n_obs:
+    if keydiff:
+        out = cache.prefill_chunk_keydiff(0, c, U.bits_to_torch(qb), U.bits_to_torch(kb), U.bits_to_torch(vb))
+        scores_ref = oc.keydiff(c, k64, v64)
+    elif n_obs:
         ob = _rand_bits(rng, (n_obs, hq, d))
         out = cache.prefill_chunk_proxy(0, c, U.bits_to_torch(qb), U.bits_to_torch(kb), U.bits_to_torch(vb),
                                         U.bits_to_torch(ob))
@@ -139,6 +142,30 @@ def test_proxy_query_scores_and_selection(hq, hkv, d, c, n, budget, chunk_max, n
     g = hq // hkv
     U.check_scores(scores_gpu, scores_ref, n_obs * g)
     np.testing.assert_allclose(scores_gpu.sum(axis=1), n_obs * g, rtol=1e-4)
+    tok = np.concatenate([oc.idx, np.broadcast_to(np.arange(c, c + n), (hkv, n))], axis=1)
+    keep = keep.cpu().numpy().astype(bool)
+    for hk in range(hkv):
+        assert np.array_equal(keep[hk], O.select_keep(scores_gpu[hk], tok[hk], budget))
+    cache.close()
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,n,budget,chunk_max", [
+    (4, 4, 64, 128, 64, 128, 64),
+    (8, 2, 128, 200, 150, 200, 256),
+    (32, 8, 128, 2048, 1024, 2048, 1024),     # the bench shape
+    (2, 2, 64, 6144, 2048, 6144, 2048),       # the candidate limit
+    (4, 2, 64, 0, 96, 32, 96),                # empty cache, block larger than the budget
+    (4, 1, 128, 37, 5, 40, 8),
+])
+def test_keydiff_scores_and_selection(hq, hkv, d, c, n, budget, chunk_max):
+    """Query-agnostic scores (minus the cosine to the mean candidate key), the attention output
+    unchanged, and the selection made from those scores."""
+    cache, oc, err, scores_ref, _ = _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed=5 * c + n, keydiff=True)
+    assert err <= U.OUT_TOL, err
+    scores_gpu, keep, dst = cache.debug_last(0)
+    scores_gpu = scores_gpu.cpu().numpy()
+    # fp32 sums of at most 8192 terms against float64: a cosine is off by a few 1e-6 at most
+    assert np.abs(scores_gpu - scores_ref).max() <= 2e-5
     tok = np.concatenate([oc.idx, np.broadcast_to(np.arange(c, c + n), (hkv, n))], axis=1)
     keep = keep.cpu().numpy().astype(bool)
     for hk in range(hkv):

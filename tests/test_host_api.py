@@ -133,7 +133,7 @@ def test_state_machine_and_counts():
         K.kvp_free_cache(h)
 
 
-def test_proxy_entry_point_follows_the_same_state_machine():
+def test_proxy_and_keydiff_entry_points_follow_the_same_state_machine():
     wl = get_workload("tiny")
     cfg = _cfg(wl)
     rc, h = K.kvp_init_cache(cfg, wl.segments, None, 0)
@@ -144,7 +144,10 @@ def test_proxy_entry_point_follows_the_same_state_machine():
         assert K.kvp_prefill_chunk_proxy(h, 0, 3, 8, 0, 0, 0, 0, 0, 4) == K.KVP_ESTATE            # tokens skipped
         count = 0
         for t0, n in chunk_ranges(wl.n_tokens, wl.chunk):
-            assert K.kvp_prefill_chunk_proxy(h, 0, t0, n, 0, 0, 0, 0, 0, 4) == K.KVP_OK
+            if (t0 // wl.chunk) % 2:
+                assert K.kvp_prefill_chunk_proxy(h, 0, t0, n, 0, 0, 0, 0, 0, 4) == K.KVP_OK
+            else:
+                assert K.kvp_prefill_chunk_keydiff(h, 0, t0, n, 0, 0, 0, 0) == K.KVP_OK
             assert K.kvp_prefill_chunk(h, 0, t0 + n, 1, 0, 0, 0, 0) == K.KVP_ESTATE               # pending
             assert K.kvp_compact(h, 0) == K.KVP_OK
             count = min(wl.budget, count + n)

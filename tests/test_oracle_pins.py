@@ -466,3 +466,25 @@ def test_proxy_scores_invariants_and_relation_to_block_scores():
     # permuting the candidates permutes the scores
     perm = rng.permutation(c + n)
     np.testing.assert_allclose(O.proxy_scores(q_obs, k_all[:, perm]), s[:, perm], rtol=1e-12)
+
+
+def test_keydiff_scores_against_loops_and_invariants():
+    rng = np.random.default_rng(31)
+    hkv, m, d = 2, 17, 6
+    k = _rand_bf16(rng, (hkv, m, d))
+    got = O.keydiff_scores(k)
+    for hk in range(hkv):
+        mu = [sum(k[hk, j, x] for j in range(m)) / m for x in range(d)]
+        nmu = math.sqrt(sum(v * v for v in mu))
+        for j in range(m):
+            dot = sum(k[hk, j, x] * mu[x] for x in range(d))
+            nk = math.sqrt(sum(k[hk, j, x] ** 2 for x in range(d)))
+            assert abs(got[hk, j] + dot / (nk * nmu)) < 1e-12
+    assert (np.abs(got) <= 1 + 1e-12).all()                      # a cosine
+    np.testing.assert_allclose(O.keydiff_scores(3.5 * k), got, rtol=1e-12)      # scale-free
+    perm = rng.permutation(m)
+    np.testing.assert_allclose(O.keydiff_scores(k[:, perm]), got[:, perm], rtol=1e-12)
+    # the key that is the anchor's own direction scores lowest, its opposite highest
+    base = np.zeros((1, 5, 3)); base[0, :, 0] = [1, 2, 3, 4, -0.5]
+    s = O.keydiff_scores(base)[0]
+    assert np.allclose(s[:4], -1) and np.isclose(s[4], 1)
