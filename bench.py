@@ -73,7 +73,7 @@ def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None, keydiff=Fa
     driver.finish()
 
 
-def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0):
+def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=4):
     import torch
     import paper_2604_16734_amd as K
     from kvp_workload import chunk_ranges
@@ -81,8 +81,9 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
     data = generate(wl, device, threads)
     ranges = chunk_ranges(wl.n_tokens, wl.chunk)
     two = streams == 2 and wl.n_layers >= 4
+    scratch_sets = max(2, min(scratch_sets, wl.n_layers))
     cache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
-                    wl.segments, merge=True, scratch_sets=2 if two else 1, device=device)
+                    wl.segments, merge=True, scratch_sets=scratch_sets if two else 1, device=device)
     driver = K.Prefill(cache, wl.n_layers, overlap=two)
     outs = [torch.empty((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=device)
             for _ in range(wl.n_layers)]
@@ -212,6 +213,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
                     help="2: kvp_compact of a layer runs on a second stream beside the next layers' kvp_prefill_chunk")
+    ap.add_argument("--scratch-sets", type=int, default=4,
+                    help="scratch sets of the cache with two streams: the main stream looks at the side stream "
+                         "once every (sets / 2) layers")
     ap.add_argument("--n-obs", type=int, default=64,
                     help="also time the prefill scored with this many proxy queries (0: skip)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -237,13 +241,15 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-    main_res = bench_workload(wl, args.steps, args.warmup, device, threads, streams=args.streams, n_obs=args.n_obs)
+    main_res = bench_workload(wl, args.steps, args.warmup, device, threads, streams=args.streams, n_obs=args.n_obs,
+                              scratch_sets=args.scratch_sets)
 
     others = {}
     if args.others:
         for w in WORKLOADS:
             if w.name != wl.name:
-                r = bench_workload(w, max(3, args.steps // 2), 2, device, threads, profile=True, streams=args.streams)
+                r = bench_workload(w, max(3, args.steps // 2), 2, device, threads, profile=True, streams=args.streams,
+                                   scratch_sets=args.scratch_sets)
                 others[w.name] = {
                     "tokens_per_s": round(r["tokens_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4),
                     "attention_tflops": round(r["attention_tflops"], 2),

@@ -161,6 +161,30 @@ int kvp_prefill_chunk_keydiff(kvp_cache* cache, int32_t layer, int32_t token_beg
  * first, then block tokens) used instead of the computed scores. */
 int kvp_compact(kvp_cache* cache, int32_t layer, const float* scores_override, void* stream);
 
+/* One block of the prefix through every layer (the body of the loop of Alg. 1,
+ * for all layers): for layer 0 .. n_layers-1, kvp_prefill_chunk (or its proxy or
+ * key-only scoring variant) followed by kvp_compact.
+ *   q, k, v, out, q_obs   HOST arrays of n_layers DEVICE pointers, shapes as for
+ *                         the per-layer calls (q_obs only read for KVP_SCORE_PROXY)
+ *   scoring               KVP_SCORE_OWN, KVP_SCORE_PROXY or KVP_SCORE_KEYDIFF
+ * With side_stream NULL (or equal to stream) everything is enqueued on `stream`
+ * in that order.  With another side_stream every kvp_compact goes there, beside
+ * the attention of the layers that follow (in a model nothing after a layer's
+ * attention reads the cache being compacted); the library orders the two
+ * streams with its own events: a layer's next block waits for that layer's
+ * compaction, and a scratch set waits for the compaction of the layer that
+ * used it last.  That needs scratch_sets >= 2 (KVP_EINVAL otherwise).  Both
+ * streams must have the default priority.  Errors as for the per-layer calls;
+ * layers before the failing one have been enqueued and advanced. */
+enum { KVP_SCORE_OWN = 0, KVP_SCORE_PROXY = 1, KVP_SCORE_KEYDIFF = 2 };
+int kvp_prefill_block(kvp_cache* cache, int32_t token_begin, int32_t n_tokens,
+                      const void* const* q, const void* const* k, const void* const* v, void* const* out,
+                      int32_t scoring, const void* const* q_obs, int32_t n_obs,
+                      void* stream, void* side_stream);
+/* Makes `stream` wait for every compaction kvp_prefill_block has put on
+ * side_stream (before the caches are read on `stream`, e.g. for decoding). */
+int kvp_prefill_join(kvp_cache* cache, void* stream, void* side_stream);
+
 /* The compressed cache of one layer (Alg. 1 line 13).  Device pointers into
  * device_buf; the first `count` slots of every head are valid; slot order
  * carries no meaning.  KVP_ESTATE while the layer is PENDING. */

@@ -87,6 +87,10 @@ def lib():
         L.kvp_prefill_chunk_proxy.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
         L.kvp_prefill_chunk_keydiff.restype = ctypes.c_int
         L.kvp_prefill_chunk_keydiff.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.kvp_prefill_block.restype = ctypes.c_int
+        L.kvp_prefill_block.argtypes = [vp, i32, i32, P(vp), P(vp), P(vp), P(vp), i32, P(vp), i32, vp, vp]
+        L.kvp_prefill_join.restype = ctypes.c_int
+        L.kvp_prefill_join.argtypes = [vp, vp, vp]
         L.kvp_compact.restype = ctypes.c_int
         L.kvp_compact.argtypes = [vp, i32, vp, vp]
         L.kvp_decode_ready.restype = ctypes.c_int
@@ -151,6 +155,25 @@ def kvp_prefill_chunk_proxy(handle, layer, token_begin, n_tokens, q, k, v, out, 
 
 def kvp_prefill_chunk_keydiff(handle, layer, token_begin, n_tokens, q, k, v, out, stream=0):
     return lib().kvp_prefill_chunk_keydiff(handle, layer, token_begin, n_tokens, q, k, v, out, stream)
+
+
+KVP_SCORE_OWN, KVP_SCORE_PROXY, KVP_SCORE_KEYDIFF = 0, 1, 2
+
+
+def _ptr_array(ptrs):
+    return (ctypes.c_void_p * len(ptrs))(*ptrs)
+
+
+def kvp_prefill_block(handle, token_begin, n_tokens, q, k, v, out, scoring=KVP_SCORE_OWN, q_obs=None, n_obs=0,
+                      stream=0, side_stream=None):
+    """q, k, v, out, q_obs: sequences of n_layers device pointers."""
+    obs = _ptr_array(q_obs) if q_obs is not None else None
+    return lib().kvp_prefill_block(handle, token_begin, n_tokens, _ptr_array(q), _ptr_array(k), _ptr_array(v),
+                                   _ptr_array(out), scoring, obs, n_obs, stream, side_stream)
+
+
+def kvp_prefill_join(handle, stream=0, side_stream=None):
+    return lib().kvp_prefill_join(handle, stream, side_stream)
 
 
 def kvp_compact(handle, layer, scores_override=None, stream=0):

@@ -116,6 +116,8 @@ struct kvp_cache {
   bool profiling = false;
   std::vector<ProfEvent> events;      // recorded, not yet read
   std::vector<hipEvent_t> pool;       // idle events
+  // kvp_prefill_block: per layer, "attention and scoring enqueued" and "compaction enqueued"
+  std::vector<hipEvent_t> attended, compacted;
 
   u16* k_cache(int l) const { return reinterpret_cast<u16*>(base + lay.k_off + (size_t)l * lay.kv_layer_bytes); }
   u16* v_cache(int l) const { return reinterpret_cast<u16*>(base + lay.v_off + (size_t)l * lay.kv_layer_bytes); }
@@ -454,6 +456,60 @@ int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void*
   return KVP_OK;
 }
 
+int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const void* const* q,
+                      const void* const* k, const void* const* v, void* const* out, int32_t scoring,
+                      const void* const* q_obs, int32_t n_obs, void* stream, void* side_stream) {
+  if (!c || !q || !k || !v || !out) return KVP_EINVAL;
+  if (scoring < KVP_SCORE_OWN || scoring > KVP_SCORE_KEYDIFF) return KVP_EINVAL;
+  if (scoring == KVP_SCORE_PROXY && !q_obs) return KVP_EINVAL;
+  const int n_layers = c->cfg.n_layers, n_sets = c->lay.n_sets;
+  const bool two = side_stream != nullptr && side_stream != stream && !c->dry;
+  if (two && n_sets < 2) return KVP_EINVAL;      // compaction beside the next layer needs a second scratch set
+  hipStream_t main = static_cast<hipStream_t>(stream), side = static_cast<hipStream_t>(side_stream);
+  // the main stream looks at the side stream once every `wait_every` layers
+  const int wait_every = n_sets >= 2 && n_sets <= n_layers ? n_sets / 2 : 1;
+  if (two && c->attended.empty()) {
+    for (std::vector<hipEvent_t>* list : {&c->attended, &c->compacted})
+      for (int l = 0; l < n_layers; ++l) {
+        hipEvent_t e;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return KVP_EDEVICE;
+        list->push_back(e);
+      }
+  }
+  for (int layer = 0; layer < n_layers; ++layer) {
+    if (two && layer % wait_every == 0) {
+      // Scratch sets: layers [layer, layer + wait_every) reuse the sets of layers
+      // [layer - n_sets, layer - n_sets + wait_every), the last of which is layer - wait_every - 1
+      // (n_sets = 2 wait_every); the side stream is in order, so its compaction covers them all.
+      // The same wait covers the other hazard (a layer's cache must have taken its previous
+      // block): that compaction is earlier still on the side stream.  Before layer 0 the index
+      // wraps to the previous block's last layers.  An event never recorded holds nobody up.
+      const int dep = ((layer - wait_every - 1) % n_layers + n_layers) % n_layers;
+      if (hipStreamWaitEvent(main, c->compacted[dep], 0) != hipSuccess) return KVP_EDEVICE;
+    }
+    const int mode = scoring == KVP_SCORE_PROXY ? kScoreProxy : scoring == KVP_SCORE_KEYDIFF ? kScoreKeydiff : kScoreOwn;
+    int rc = prefill_impl(c, layer, token_begin, n_tokens, q[layer], k[layer], v[layer], out[layer],
+                          mode == kScoreProxy ? q_obs[layer] : nullptr, n_obs, mode, stream);
+    if (rc) return rc;
+    if (two) {
+      if (hipEventRecord(c->attended[layer], main) != hipSuccess) return KVP_EDEVICE;
+      if (hipStreamWaitEvent(side, c->attended[layer], 0) != hipSuccess) return KVP_EDEVICE;
+    }
+    rc = kvp_compact(c, layer, nullptr, two ? side_stream : stream);
+    if (rc) return rc;
+    if (two && hipEventRecord(c->compacted[layer], side) != hipSuccess) return KVP_EDEVICE;
+  }
+  return KVP_OK;
+}
+
+int kvp_prefill_join(kvp_cache* c, void* stream, void* side_stream) {
+  if (!c) return KVP_EINVAL;
+  if (c->dry || !side_stream || side_stream == stream || c->compacted.empty()) return KVP_OK;
+  for (hipEvent_t e : c->compacted)
+    if (hipStreamWaitEvent(static_cast<hipStream_t>(stream), e, 0) != hipSuccess) return KVP_EDEVICE;
+  return KVP_OK;
+}
+
 int kvp_decode_ready(kvp_cache* c, int32_t layer, kvp_view* out) {
   if (!c || !out || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
   const Layer& L = c->layers[layer];
@@ -528,6 +584,8 @@ void kvp_free_cache(kvp_cache* c) {
     (void)hipEventDestroy(pe.stop);
   }
   for (hipEvent_t e : c->pool) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->attended) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->compacted) (void)hipEventDestroy(e);
   delete c;
 }
 

@@ -6,15 +6,15 @@ order, but the compaction of a layer has nothing to do with the attention of the
 next layer: in a model, what follows a layer's attention is its MLP and the next
 layer, and none of that reads the cache being compacted.  `Prefill` therefore can
 put every kvp_compact on a second stream, where it runs beside the
-kvp_prefill_chunk calls that follow; events keep the two hazards in order:
-
-  * a layer's next block waits for that layer's compaction, and
-  * a scratch set (layer mod scratch_sets) waits for the compaction of the last
-    layer that used it.
+kvp_prefill_chunk calls that follow.  The loop over the layers and the events
+between the two streams live in the library (kvp_prefill_block): one call per
+block, so that the host keeps ahead of the GPU.
 
 Both streams have the default priority.
 """
 from __future__ import annotations
+
+from . import binding as B
 
 
 class Prefill:
@@ -27,16 +27,13 @@ class Prefill:
         self.cache = cache
         self.n_layers = n_layers
         self.overlap = bool(overlap)
-        self.n_sets = int(cache.cfg.scratch_sets) or 1
-        if self.overlap and self.n_sets < 2:
+        if self.overlap and (int(cache.cfg.scratch_sets) or 1) < 2:
             raise ValueError("overlap needs a cache created with scratch_sets >= 2")
-        if self.overlap:
-            dev = cache.device
-            self.side = torch.cuda.Stream(device=dev)
-            self.compacted = [torch.cuda.Event() for _ in range(n_layers)]
-            self.attended = [torch.cuda.Event() for _ in range(n_layers)]
-            for e in self.compacted:
-                e.record(torch.cuda.current_stream(dev))
+        self.side = torch.cuda.Stream(device=cache.device) if self.overlap else None
+
+    def _streams(self):
+        main = self.torch.cuda.current_stream(self.cache.device).cuda_stream
+        return main, (self.side.cuda_stream if self.side is not None else None)
 
     def block(self, t0, qkv_of_layer, out_of_layer=None, obs_of_layer=None, keydiff=False):
         """One block of the prefix through all layers.  `qkv_of_layer(l)` gives the block's
@@ -44,35 +41,32 @@ class Prefill:
         The candidates are scored by the block's own queries, or by the proxy queries
         `obs_of_layer(l)`, or (`keydiff`) by the keys alone.  Returns the list of outputs."""
         cache, torch = self.cache, self.torch
-        outs = []
-
-        def attend(layer, q, k, v):
-            out = out_of_layer(layer) if out_of_layer else None
-            if keydiff:
-                return cache.prefill_chunk_keydiff(layer, t0, q, k, v, out=out)
-            if obs_of_layer is not None:
-                return cache.prefill_chunk_proxy(layer, t0, q, k, v, obs_of_layer(layer), out=out)
-            return cache.prefill_chunk(layer, t0, q, k, v, out=out)
-        if not self.overlap:
-            for layer in range(self.n_layers):
-                q, k, v = qkv_of_layer(layer)
-                outs.append(attend(layer, q, k, v))
-                cache.compact(layer)
-            return outs
-        main = torch.cuda.current_stream(cache.device)
+        bf = torch.bfloat16
+        qs, ks, vs, outs, obs = [], [], [], [], []
+        n = None
         for layer in range(self.n_layers):
             q, k, v = qkv_of_layer(layer)
-            main.wait_event(self.compacted[layer])
-            if self.n_layers > self.n_sets:
-                main.wait_event(self.compacted[(layer - self.n_sets) % self.n_layers])
-            outs.append(attend(layer, q, k, v))
-            self.attended[layer].record(main)
-            self.side.wait_event(self.attended[layer])
-            cache.compact(layer, stream=self.side)
-            self.compacted[layer].record(self.side)
+            n = q.shape[0]
+            assert q.shape == (n, cache.cfg.n_q_heads, cache.cfg.head_dim)
+            assert k.shape == v.shape == (n, cache.cfg.n_kv_heads, cache.cfg.head_dim)
+            out = out_of_layer(layer) if out_of_layer else None
+            if out is None:
+                out = torch.empty_like(q)
+            assert out.shape == q.shape
+            qs.append(q); ks.append(k); vs.append(v); outs.append(out)
+            if obs_of_layer is not None and not keydiff:
+                o = obs_of_layer(layer)
+                assert o.shape[1:] == q.shape[1:] and (not obs or o.shape[0] == obs[0].shape[0])
+                obs.append(o)
+        scoring = B.KVP_SCORE_KEYDIFF if keydiff else (B.KVP_SCORE_PROXY if obs else B.KVP_SCORE_OWN)
+        ptr = lambda ts: [cache._ptr(t, bf) for t in ts]
+        main, side = self._streams()
+        rc = B.kvp_prefill_block(cache.handle, t0, n, ptr(qs), ptr(ks), ptr(vs), ptr(outs), scoring,
+                                 ptr(obs) if obs else None, obs[0].shape[0] if obs else 0, main, side)
+        B._check(rc, "kvp_prefill_block")
         return outs
 
     def finish(self):
         """Make the current stream wait for the compactions still in flight."""
-        if self.overlap:
-            self.torch.cuda.current_stream(self.cache.device).wait_stream(self.side)
+        main, side = self._streams()
+        B._check(B.kvp_prefill_join(self.cache.handle, main, side), "kvp_prefill_join")

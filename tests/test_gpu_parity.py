@@ -383,8 +383,8 @@ def test_free_running_invariants(name):
         assert np.array_equal(results[0][layer][1], results[1][layer][1])
 
 
-@pytest.mark.parametrize("name", ["tiled_image", "video"])
-def test_compaction_on_a_second_stream_changes_nothing(name):
+@pytest.mark.parametrize("name,sets", [("tiled_image", 2), ("video", 2), ("tiled_image", 3), ("video", 4), ("tiled_image", 6)])
+def test_compaction_on_a_second_stream_changes_nothing(name, sets):
     """The whole prefill with every kvp_compact on a second stream (two scratch sets, events
     between the streams) must leave bit for bit the caches and outputs of the in-order run."""
     wl = get_workload(name)
@@ -394,7 +394,7 @@ def test_compaction_on_a_second_stream_changes_nothing(name):
     results = []
     for overlap in (False, True):
         cache = K.Cache(layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments,
-                        merge=True, scratch_sets=2 if overlap else 1, device=DEV)
+                        merge=True, scratch_sets=sets if overlap else 1, device=DEV)
         driver = K.Prefill(cache, layers, overlap=overlap)
         outs = [torch.zeros((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=DEV)
                 for _ in range(layers)]
