@@ -472,7 +472,7 @@ int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const
     for (std::vector<hipEvent_t>* list : {&c->attended, &c->compacted})
       for (int l = 0; l < n_layers; ++l) {
         hipEvent_t e;
-        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return KVP_EDEVICE;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice) != hipSuccess) return KVP_EDEVICE;
         list->push_back(e);
       }
   }
