@@ -80,8 +80,9 @@ def compare_state(cache, layer, oc, merged_ulp=1):
 
 
 def lockstep_layer(wl, layer, cache, qb, kb, vb, merge, chunk=None, budget=None, max_chunks=None,
-                   device="cuda:0", stats=None):
-    """Runs one layer of `wl` through GPU and oracle in lock-step; asserts parity."""
+                   device="cuda:0", stats=None, blocks=None):
+    """Runs one layer of `wl` through GPU and oracle in lock-step; asserts parity.
+    `blocks`: explicit (first token, length) pairs instead of fixed-size blocks."""
     chunk = chunk or wl.chunk
     budget = budget or wl.budget
     q64, k64, v64 = (bf16_bits_to_f32(x).astype(np.float64) for x in (qb, kb, vb))
@@ -89,7 +90,7 @@ def lockstep_layer(wl, layer, cache, qb, kb, vb, merge, chunk=None, budget=None,
     oc = O.LayerCache(wl.n_kv_heads, wl.head_dim, budget, wl.segments, merge)
     g = wl.n_q_heads // wl.n_kv_heads
     worst_out, worst_sc, n_merged = 0.0, 0.0, 0
-    for ci, (t0, n) in enumerate(chunk_ranges(wl.n_tokens, chunk)):
+    for ci, (t0, n) in enumerate(blocks if blocks is not None else chunk_ranges(wl.n_tokens, chunk)):
         if max_chunks is not None and ci >= max_chunks:
             break
         upload_state(cache, layer, oc)

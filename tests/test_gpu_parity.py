@@ -319,6 +319,31 @@ def test_degenerate_shapes_lockstep(hq, hkv, d, chunk, budget, segs):
         cache.close()
 
 
+def test_structure_aligned_blocks_and_bulk_first_pass_lockstep():
+    """Blocks cut at frame boundaries, of different lengths, after a first block that fills the
+    whole budget in one causal pass (Sec. 3.1 and the hybrid execution of Sec. 4.3): any block
+    length up to chunk_max goes through the same kernels."""
+    gh, gw, frames, n_text = 14, 14, 24, 40                     # 196-token frames
+    per = gh * gw
+    segs = (Segment(0, per * frames, 1, gh, gw, frames, 1), Segment(per * frames, n_text, 0))
+    budget = 4 * per                                            # 784 = four frames
+    wl = Workload("aligned", 1, 8, 2, 128, budget, budget, segs, "shared")
+    # bulk first pass of `budget` tokens, then blocks of one, three, two ... frames, then the text
+    lengths = [4 * per, per, 3 * per, 2 * per, 4 * per, per, 2 * per, 3 * per, 4 * per, n_text]
+    assert sum(lengths) == wl.n_tokens
+    blocks, t0 = [], 0
+    for n in lengths:
+        blocks.append((t0, n))
+        t0 += n
+    qb, kb, vb = layer_inputs(wl, 0, seed0=17)
+    for merge in (False, True):
+        cache = K.Cache(1, 8, 2, 128, budget, budget, segs, merge=merge, device=DEV)
+        stats = {}
+        U.lockstep_layer(wl, 0, cache, qb, kb, vb, merge, stats=stats, blocks=blocks)
+        assert merge == (stats["merged"] > 0)
+        cache.close()
+
+
 def test_budget_at_least_prefix_is_full_attention():
     """Alg. 1 line 8 never fires: the GPU path must equal plain causal attention."""
     wl = get_workload("tiny")
