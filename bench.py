@@ -131,7 +131,42 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         bulk = {"first_block": wl.budget, "tokens_per_s": round(wl.n_tokens / t_bulk, 1), "ms_per_step": round(1e3 * t_bulk, 4)}
         bcache.close()
         del bouts
+    # generation over the compressed caches (Eq. 1 with one query row): the attention of one new
+    # token in every layer, its own key and value being the whole tail
+    run_steps(driver, cache, wl, data, ranges, 1, outs)
+    torch.cuda.synchronize()
+    dq = [x[0][0].contiguous() for x in data]
+    dk = [x[1][:1].contiguous() for x in data]
+    dv = [x[2][:1].contiguous() for x in data]
+    dout = torch.empty_like(dq[0])
+    ptrs = [(dq[l].data_ptr(), dk[l].data_ptr(), dv[l].data_ptr()) for l in range(wl.n_layers)]
+    stream = torch.cuda.current_stream(device).cuda_stream
+
+    def decode_tokens(count):
+        for _ in range(count):
+            for l, (pq, pk, pv) in enumerate(ptrs):
+                rc = K.kvp_decode_step(cache.handle, l, pq, pk, pv, 1, dout.data_ptr(), stream)
+                if rc:
+                    raise K.KvpError(rc, "kvp_decode_step")
+    decode_tokens(2)
+    torch.cuda.synchronize()
+    n_dec = 20
+    t_dec = time.perf_counter()
+    decode_tokens(n_dec)
+    torch.cuda.synchronize()
+    t_dec = (time.perf_counter() - t_dec) / n_dec
+    cache.profile_enable(True)
+    decode_tokens(2)
+    torch.cuda.synchronize()
+    dec_launches, dec_ms = cache.profile_read()["decode"]
+    cache.profile_enable(False)
+    kept = min(wl.budget, wl.n_tokens)
+    dec_bytes = 2 * wl.n_kv_heads * (kept + 1) * wl.head_dim * 2      # K and V rows of one layer, read once
+    decode = {"us_per_token_all_layers": round(1e6 * t_dec, 2), "us_per_layer_on_device": round(1e3 * dec_ms / dec_launches, 3),
+              "bytes_per_layer": dec_bytes, "GBps_on_device": round(dec_bytes / (1e-3 * dec_ms / dec_launches) / 1e9, 1),
+              "keys": kept + 1}
     res = {
+        "decode_step": decode,
         "bulk_first_pass": bulk,
         "keydiff_scoring": {"tokens_per_s": round(wl.n_tokens / t_kd, 1), "ms_per_step": round(1e3 * t_kd, 4)},
         "proxy_scoring": proxy,
@@ -322,6 +357,7 @@ def main():
         "proxy_query_scoring": main_res["proxy_scoring"],
         "keydiff_scoring": main_res["keydiff_scoring"],
         "bulk_first_pass": main_res["bulk_first_pass"],
+        "decode_step": main_res["decode_step"],
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)

@@ -199,6 +199,23 @@ typedef struct kvp_view {
 } kvp_view;
 int kvp_decode_ready(kvp_cache* cache, int32_t layer, kvp_view* out);
 
+/* One decode step of one layer over the compressed cache (Eq. 1 of Sec. 2.1 with
+ * one query row per head; generation reuses the cached keys and values, ibid.).
+ * The keys are the layer's `count` cache entries followed by the `n_tail` tokens
+ * generated so far, the current token last: the caller keeps that tail, the
+ * cache itself is not changed and the layer stays READY.
+ *   q       [n_q_heads, head_dim]          bf16, the current token's queries
+ *   k_tail  [n_tail, n_kv_heads, head_dim] bf16 (row n_tail - 1 is the current token)
+ *   v_tail  same shape
+ *   out     [n_q_heads, head_dim]          bf16
+ * out[h] = softmax(scale * q[h] . K^T) V over all count + n_tail keys of KV
+ * head h / (n_q_heads / n_kv_heads), accumulated in fp32 and rounded once.
+ * Uses the layer's scratch set: KVP_ESTATE if the layer is PENDING or another
+ * layer's block is pending in that set.  KVP_EINVAL for n_tail < 1, n_tail >
+ * 2^20, a null pointer, or more than 16 query heads per KV head. */
+int kvp_decode_step(kvp_cache* cache, int32_t layer, const void* q, const void* k_tail, const void* v_tail,
+                    int32_t n_tail, void* out, void* stream);
+
 /* Resume: declare that the caller has written `count` valid slots per head
  * into the layer's K, V, token_idx and weight (through the kvp_view pointers)
  * and that the next block starts at `next_token`.  Layer becomes READY. */
@@ -221,7 +238,7 @@ int kvp_debug_last(kvp_cache* cache, int32_t layer, const float** scores, const 
  * recorded events, adds them up per kernel kind and clears them. */
 enum {
   KVP_K_ATTENTION = 0, KVP_K_COLSUM = 1, KVP_K_SELECT = 2, KVP_K_MERGE = 3,
-  KVP_K_MOVE = 4, KVP_K_ROWSTAT = 5, KVP_K_KEYDIFF = 6, KVP_K_COUNT = 7
+  KVP_K_MOVE = 4, KVP_K_ROWSTAT = 5, KVP_K_KEYDIFF = 6, KVP_K_DECODE = 7, KVP_K_COUNT = 8
 };
 typedef struct kvp_kernel_stat {
   int64_t launches;

@@ -19,6 +19,8 @@ What follows the paper, and where:
   * ``proxy_scores``      Eq. 4 with the proxy queries of Sec. 3.2 (every
                           candidate visible to every proxy query).
   * ``keydiff_scores``    the query-agnostic strategy of Sec. 3.2.
+  * ``decode_step``       Eq. 1 (Sec. 2.1) for the one query row of a
+                          generation step over cache U generated tokens.
 
 Readings where the paper is silent (each is a choice of this build):
   * the observation queries of Eq. 4 are the block's own queries; their
@@ -172,6 +174,39 @@ def proxy_scores(q_obs, k_all, scale=None):
         p /= p.sum(axis=1, keepdims=True)
         scores[hk] += p.sum(axis=0)
     return scores
+
+
+# ----------------------------------------------------------------------------
+# Eq. 1 for one generation step
+# ----------------------------------------------------------------------------
+def decode_step(q, k_all, v_all, scale=None):
+    """Eq. 1 with one query row per head (Sec. 2.1: during generation only the
+    current token's query is new, the keys and values of all earlier tokens are
+    reused).  The current token sees every key it is given.
+
+    q      [Hq, d]
+    k_all  [Hkv, m, d]   cached keys, then the keys of the generated tokens, the current one last
+    v_all  [Hkv, m, d]
+
+    Returns ``out [Hq, d]`` float64.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k_all = np.asarray(k_all, dtype=np.float64)
+    v_all = np.asarray(v_all, dtype=np.float64)
+    hq, d = q.shape
+    hkv = k_all.shape[0]
+    assert hq % hkv == 0
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((hq, d), dtype=np.float64)
+    for h in range(hq):
+        hk = h // g
+        s = scale * (k_all[hk] @ q[h])                    # [m]
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        out[h] = p @ v_all[hk]
+    return out
 
 
 # ----------------------------------------------------------------------------

@@ -16,7 +16,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "kvp.h")
 KVP_OK, KVP_EINVAL, KVP_ESTATE, KVP_ENOMEM, KVP_EDEVICE = 0, -1, -2, -3, -4
 KVP_TEXT, KVP_VISUAL = 0, 1
 KVP_FLAG_DRY_RUN = 1
-KERNEL_KINDS = ("attention", "colsum", "select", "merge", "move", "rowstat", "keydiff")
+KERNEL_KINDS = ("attention", "colsum", "select", "merge", "move", "rowstat", "keydiff", "decode")
 
 
 class KvpError(RuntimeError):
@@ -93,6 +93,8 @@ def lib():
         L.kvp_prefill_join.argtypes = [vp, vp, vp]
         L.kvp_compact.restype = ctypes.c_int
         L.kvp_compact.argtypes = [vp, i32, vp, vp]
+        L.kvp_decode_step.restype = ctypes.c_int
+        L.kvp_decode_step.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp]
         L.kvp_decode_ready.restype = ctypes.c_int
         L.kvp_decode_ready.argtypes = [vp, i32, P(KvpView)]
         L.kvp_set_state.restype = ctypes.c_int
@@ -155,6 +157,10 @@ def kvp_prefill_chunk_proxy(handle, layer, token_begin, n_tokens, q, k, v, out, 
 
 def kvp_prefill_chunk_keydiff(handle, layer, token_begin, n_tokens, q, k, v, out, stream=0):
     return lib().kvp_prefill_chunk_keydiff(handle, layer, token_begin, n_tokens, q, k, v, out, stream)
+
+
+def kvp_decode_step(handle, layer, q, k_tail, v_tail, n_tail, out, stream=0):
+    return lib().kvp_decode_step(handle, layer, q, k_tail, v_tail, n_tail, out, stream)
 
 
 KVP_SCORE_OWN, KVP_SCORE_PROXY, KVP_SCORE_KEYDIFF = 0, 1, 2
@@ -278,6 +284,20 @@ class Cache:
         rc = kvp_prefill_chunk_keydiff(self.handle, layer, token_begin, n, self._ptr(q, bf), self._ptr(k, bf),
                                        self._ptr(v, bf), self._ptr(out, bf), self._stream(stream))
         _check(rc, "kvp_prefill_chunk_keydiff")
+        return out
+
+    def decode_step(self, layer, q, k_tail, v_tail, out=None, stream=None):
+        """q [Hq, d]; k_tail, v_tail [n_tail, Hkv, d] (the generated tokens, the current one last)."""
+        bf = self.torch.bfloat16
+        assert q.shape == (self.cfg.n_q_heads, self.cfg.head_dim)
+        n_tail = k_tail.shape[0]
+        assert k_tail.shape == v_tail.shape == (n_tail, self.cfg.n_kv_heads, self.cfg.head_dim)
+        if out is None:
+            out = self.torch.empty_like(q)
+        assert out.shape == q.shape
+        rc = kvp_decode_step(self.handle, layer, self._ptr(q, bf), self._ptr(k_tail, bf), self._ptr(v_tail, bf),
+                             n_tail, self._ptr(out, bf), self._stream(stream))
+        _check(rc, "kvp_decode_step")
         return out
 
     def prefill_chunk_proxy(self, layer, token_begin, q, k, v, q_obs, out=None, stream=None):

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvp.so")
-SOURCES = ["attention.hip", "colsum.hip", "rowstat.hip", "keydiff.hip", "select.hip", "compact.hip", "kvp.cpp"]
+SOURCES = ["attention.hip", "colsum.hip", "rowstat.hip", "keydiff.hip", "decode.hip", "select.hip", "compact.hip", "kvp.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed fp32 arithmetic is kept out of the generated code on purpose

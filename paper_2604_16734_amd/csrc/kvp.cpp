@@ -249,6 +249,7 @@ const char* kvp_kernel_name(int32_t kind) {
     case KVP_K_MOVE: return "move";
     case KVP_K_ROWSTAT: return "rowstat";
     case KVP_K_KEYDIFF: return "keydiff";
+    case KVP_K_DECODE: return "decode";
     default: return "?";
   }
 }
@@ -522,6 +523,35 @@ int kvp_decode_ready(kvp_cache* c, int32_t layer, kvp_view* out) {
   out->budget = c->cfg.budget;
   out->next_token = L.next_token;
   return KVP_OK;
+}
+
+int kvp_decode_step(kvp_cache* c, int32_t layer, const void* q, const void* k_tail, const void* v_tail,
+                    int32_t n_tail, void* out, void* stream) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  if (n_tail < 1 || n_tail > (1 << 20)) return KVP_EINVAL;
+  if (!c->dry && (!q || !k_tail || !v_tail || !out)) return KVP_EINVAL;
+  const kvp_config& cfg = c->cfg;
+  if (cfg.n_q_heads / cfg.n_kv_heads > decode_max_group()) return KVP_EINVAL;
+  const Layer& L = c->layers[layer];
+  if (L.state != READY) return KVP_ESTATE;
+  if (c->set_owner[layer % c->lay.n_sets] != -1) return KVP_ESTATE;
+  const Layout& lay = c->lay;
+  DecodeArgs da{};
+  da.q = static_cast<const u16*>(q);
+  da.k_tail = static_cast<const u16*>(k_tail);
+  da.v_tail = static_cast<const u16*>(v_tail);
+  da.out = static_cast<u16*>(out);
+  da.k_cache = c->k_cache(layer);
+  da.v_cache = c->v_cache(layer);
+  da.partial = reinterpret_cast<float*>(c->set(layer) + lay.partial_off);
+  da.c = L.count; da.n_tail = n_tail;
+  da.n_q_heads = cfg.n_q_heads; da.n_kv_heads = cfg.n_kv_heads; da.budget = cfg.budget;
+  da.scale_log2 = c->scale * 1.4426950408889634f;
+  const size_t have = (size_t)cfg.n_kv_heads * lay.max_partials * lay.cand_stride;   // floats
+  da.n_splits = decode_splits((long long)L.count + n_tail, cfg.head_dim, have, cfg.n_q_heads);
+  if (da.n_splits < 1) return KVP_ENOMEM;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  return launch(c, KVP_K_DECODE, s, [&] { return launch_decode(da, cfg.head_dim, s); });
 }
 
 int kvp_set_state(kvp_cache* c, int32_t layer, int32_t count, int32_t next_token) {

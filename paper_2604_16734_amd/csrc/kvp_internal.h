@@ -79,6 +79,22 @@ struct KeydiffArgs {
 int keydiff_slices(int n_cand);
 hipError_t launch_keydiff(KeydiffArgs a, int head_dim, hipStream_t s);
 
+// One decode step of one layer (decode.hip).
+struct DecodeArgs {
+  const u16* q;        // [Hq, D]
+  const u16* k_tail;   // [n_tail, Hkv, D]
+  const u16* v_tail;
+  u16* out;            // [Hq, D]
+  const u16* k_cache;  // this layer: [Hkv, M, D]
+  const u16* v_cache;
+  float* partial;      // [Hq, n_splits, D + 2] scratch: unnormalised output, maximum, sum
+  int c, n_tail, n_q_heads, n_kv_heads, budget, n_splits;
+  float scale_log2;
+};
+int decode_max_group();
+int decode_splits(long long n_keys, int head_dim, size_t scratch_floats, int n_q_heads);
+hipError_t launch_decode(const DecodeArgs& a, int head_dim, hipStream_t s);
+
 // Device copy of one prefix segment.
 struct Seg {
   int begin, n, kind, gh, gw, planes, temporal;

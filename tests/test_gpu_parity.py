@@ -202,6 +202,62 @@ def test_runaway_logits_take_the_careful_path(hq, hkv, d, c, n):
     cache.close()
 
 
+@pytest.mark.parametrize("hq,hkv,d,c,n_tail,budget,chunk_max,scale", [
+    (4, 4, 64, 0, 1, 256, 64, 0.0),          # nothing cached: the current token alone
+    (4, 2, 128, 63, 1, 256, 64, 0.0),        # exactly one 64-key group
+    (8, 2, 128, 193, 7, 256, 64, 0.0),       # ragged groups, a short tail
+    (4, 4, 64, 300, 70, 512, 128, 0.25),     # the tail spans a group boundary; explicit scale
+    (32, 8, 128, 2048, 1, 2048, 1024, 0.0),  # the bench shape
+    (32, 8, 128, 2048, 513, 2048, 1024, 0.0),
+    (28, 4, 128, 1024, 33, 1024, 512, 0.0),  # seven query heads per KV head
+    (16, 1, 64, 100, 3, 128, 16, 0.0),       # sixteen per KV head, little scratch
+    (2, 2, 64, 6144, 5000, 6144, 2048, 0.0),  # many groups per wave
+])
+def test_decode_step(hq, hkv, d, c, n_tail, budget, chunk_max, scale):
+    """One generation step over a preloaded cache and a tail of generated tokens."""
+    rng = np.random.default_rng(1000 + c + n_tail)
+    cache = K.Cache(1, hq, hkv, d, budget, chunk_max, [Segment(0, 100000, 0)], merge=False, softmax_scale=scale, device=DEV)
+    oc = O.LayerCache(hkv, d, budget)
+    if c:
+        kb0, vb0 = _rand_bits(rng, (c, hkv, d)), _rand_bits(rng, (c, hkv, d))
+        oc.compact(0, O.bf16_bits_to_f64(kb0), O.bf16_bits_to_f64(vb0), np.zeros((hkv, c), dtype=np.float32))
+    U.upload_state(cache, 0, oc)
+    cache.set_state(0, c, c)
+    qb, kb, vb = _rand_bits(rng, (hq, d), 2.0), _rand_bits(rng, (n_tail, hkv, d)), _rand_bits(rng, (n_tail, hkv, d))
+    q64, k64, v64 = (O.bf16_bits_to_f64(x) for x in (qb, kb, vb))
+    _, _, k_all, v_all = oc.candidates(c, k64, v64)
+    ref = O.decode_step(q64, k_all, v_all, scale or None)
+    out = cache.decode_step(0, U.bits_to_torch(qb), U.bits_to_torch(kb), U.bits_to_torch(vb))
+    err = U.out_rel_err(U.torch_bf16_to_f64(out), ref)
+    assert err <= U.OUT_TOL, err
+    # the cache is untouched: the same call again gives the same bits, and so does the
+    # block entry point for a one-row block when the tail is the current token alone
+    again = cache.decode_step(0, U.bits_to_torch(qb), U.bits_to_torch(kb), U.bits_to_torch(vb))
+    assert torch.equal(out, again)
+    if n_tail == 1 and c < budget:
+        blk = cache.prefill_chunk(0, c, U.bits_to_torch(qb)[None], U.bits_to_torch(kb), U.bits_to_torch(vb))
+        assert U.out_rel_err(U.torch_bf16_to_f64(blk[0]), ref) <= U.OUT_TOL
+    cache.close()
+
+
+def test_decode_step_after_prefill():
+    """Prefill a layer block by block, then generate three tokens over what it kept."""
+    wl = get_workload("tiled_image")
+    cache = K.Cache(1, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments, merge=True, device=DEV)
+    qb, kb, vb = layer_inputs(wl, 0)
+    oc = U.lockstep_layer(wl, 0, cache, qb, kb, vb, True)
+    rng = np.random.default_rng(5)
+    hq, hkv, d = wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    kt, vt = _rand_bits(rng, (3, hkv, d)), _rand_bits(rng, (3, hkv, d))
+    for step in range(1, 4):
+        qb = _rand_bits(rng, (hq, d), 2.0)
+        _, _, k_all, v_all = oc.candidates(wl.n_tokens, O.bf16_bits_to_f64(kt[:step]), O.bf16_bits_to_f64(vt[:step]))
+        ref = O.decode_step(O.bf16_bits_to_f64(qb), k_all, v_all)
+        out = cache.decode_step(0, U.bits_to_torch(qb), U.bits_to_torch(kt[:step]), U.bits_to_torch(vt[:step]))
+        assert U.out_rel_err(U.torch_bf16_to_f64(out), ref) <= U.OUT_TOL
+    cache.close()
+
+
 def test_select_ties_and_override():
     """All scores equal: the lowest token indices stay (ties to the lower index)."""
     hq = hkv = 2

@@ -157,6 +157,28 @@ def test_proxy_and_keydiff_entry_points_follow_the_same_state_machine():
         K.kvp_free_cache(h)
 
 
+def test_decode_step_state_machine():
+    wl = get_workload("single_image")
+    rc, h = K.kvp_init_cache(_cfg(wl, sets=2), wl.segments, None, 0)
+    assert rc == K.KVP_OK
+    try:
+        assert K.kvp_decode_step(h, 0, 0, 0, 0, 1, 0) == K.KVP_OK                # an empty cache: the tail alone
+        assert K.kvp_decode_step(h, 0, 0, 0, 0, 0, 0) == K.KVP_EINVAL            # no current token
+        assert K.kvp_decode_step(h, 0, 0, 0, 0, (1 << 20) + 1, 0) == K.KVP_EINVAL
+        assert K.kvp_decode_step(h, wl.n_layers, 0, 0, 0, 1, 0) == K.KVP_EINVAL
+        assert K.kvp_prefill_chunk(h, 0, 0, 16, 0, 0, 0, 0) == K.KVP_OK
+        assert K.kvp_decode_step(h, 0, 0, 0, 0, 1, 0) == K.KVP_ESTATE            # the layer is pending
+        assert K.kvp_decode_step(h, 2, 0, 0, 0, 1, 0) == K.KVP_ESTATE            # its scratch set is taken
+        assert K.kvp_decode_step(h, 1, 0, 0, 0, 1, 0) == K.KVP_OK                # the other set is free
+        assert K.kvp_compact(h, 0) == K.KVP_OK
+        rc, before = K.kvp_decode_ready(h, 0)
+        assert K.kvp_decode_step(h, 0, 0, 0, 0, 3, 0) == K.KVP_OK
+        rc, after = K.kvp_decode_ready(h, 0)
+        assert (after.count, after.next_token) == (before.count, before.next_token) == (16, 16)
+    finally:
+        K.kvp_free_cache(h)
+
+
 def test_scratch_sets_gate_pending_layers():
     wl = get_workload("single_image")
     for sets, second_ok in ((1, False), (2, True)):

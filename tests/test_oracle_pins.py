@@ -488,3 +488,68 @@ def test_keydiff_scores_against_loops_and_invariants():
     base = np.zeros((1, 5, 3)); base[0, :, 0] = [1, 2, 3, 4, -0.5]
     s = O.keydiff_scores(base)[0]
     assert np.allclose(s[:4], -1) and np.isclose(s[4], 1)
+
+
+# ----------------------------------------------------------------------------
+# one generation step (Eq. 1 with one query row)
+# ----------------------------------------------------------------------------
+def test_decode_step_against_library_softmax_loops_and_the_block_routine():
+    rng = np.random.default_rng(77)
+    hq, hkv, d, m = 6, 2, 8, 19
+    g = hq // hkv
+    q = rng.standard_normal((hq, d))
+    k = rng.standard_normal((hkv, m, d))
+    v = rng.standard_normal((hkv, m, d))
+    from scipy.special import softmax
+    got = O.decode_step(q, k, v)
+    # library softmax, one head at a time
+    for h in range(hq):
+        hk = h // g
+        w = softmax(k[hk] @ q[h] / np.sqrt(d))
+        np.testing.assert_allclose(got[h], w @ v[hk], rtol=1e-12, atol=1e-14)
+    # scalar loops from the definition
+    for h in (0, 3, 5):
+        hk = h // g
+        logit = [sum(q[h, x] * k[hk, j, x] for x in range(d)) / math.sqrt(d) for j in range(m)]
+        z = sum(math.exp(t) for t in logit)
+        for x in (0, d - 1):
+            want = sum(math.exp(logit[j]) / z * v[hk, j, x] for j in range(m))
+            assert abs(got[h, x] - want) < 1e-12
+    # a one-row block over a cache of m - 1 entries is the same computation
+    out_block, _ = O.attend_chunk(q[None], k, v, m - 1)
+    np.testing.assert_allclose(got, out_block[0], rtol=1e-12, atol=1e-14)
+    # the last row of a longer block sees everything as well
+    n = 5
+    qb = rng.standard_normal((n, hq, d))
+    qb[-1] = q
+    out_block, _ = O.attend_chunk(qb, k, v, m - n)
+    np.testing.assert_allclose(got, out_block[-1], rtol=1e-12, atol=1e-14)
+
+
+def test_decode_step_invariants():
+    rng = np.random.default_rng(78)
+    hq, hkv, d, m = 4, 2, 16, 33
+    q = rng.standard_normal((hq, d))
+    k = rng.standard_normal((hkv, m, d))
+    v = rng.standard_normal((hkv, m, d))
+    got = O.decode_step(q, k, v)
+    # equal values: the output is that value whatever the weights are
+    vc = np.broadcast_to(rng.standard_normal((hkv, 1, d)), v.shape)
+    np.testing.assert_allclose(O.decode_step(q, k, vc), np.repeat(vc[:, 0], hq // hkv, axis=0), rtol=1e-12)
+    # zero scale: the plain mean of the values
+    np.testing.assert_allclose(O.decode_step(q, k, v, scale=0.0), np.repeat(v.mean(axis=1), hq // hkv, axis=0), rtol=1e-12)
+    # the order of the keys carries no meaning
+    perm = rng.permutation(m)
+    np.testing.assert_allclose(O.decode_step(q, k[:, perm], v[:, perm]), got, rtol=1e-12, atol=1e-14)
+    # one key: its value
+    np.testing.assert_allclose(O.decode_step(q, k[:, :1], v[:, :1]), np.repeat(v[:, 0], hq // hkv, axis=0), rtol=1e-12)
+    # a key whose logit dwarfs the rest takes all the weight
+    kb = k.copy()
+    kb[:, 7] = 0
+    qb = np.zeros_like(q); qb[:, 0] = 1.0
+    kb[:, :, 0] = -50.0; kb[:, 7, 0] = 50.0
+    np.testing.assert_allclose(O.decode_step(qb, kb, v, scale=1.0), np.repeat(v[:, 7], hq // hkv, axis=0), rtol=1e-12, atol=1e-12)
+    # convexity: every output channel lies between the extremes of that channel's values
+    for h in range(hq):
+        hk = h // (hq // hkv)
+        assert np.all(got[h] <= v[hk].max(axis=0) + 1e-12) and np.all(got[h] >= v[hk].min(axis=0) - 1e-12)
