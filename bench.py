@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, vendor figure
 # HBM bytes per attention launch (fetch + write) at the long_video steady state, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (launch-weighted mean,
 # counters scaled by what they read for a plain 256 MiB copy); None for a workload not measured
-ATTENTION_TRAFFIC_BYTES = {"long_video": 66626329}
+ATTENTION_TRAFFIC_BYTES = {"long_video": 67006458}
 
 
 def attention_flops(wl, t0_n_pairs):
@@ -73,7 +73,7 @@ def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None, keydiff=Fa
     driver.finish()
 
 
-def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=4):
+def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=4, variants=True):
     import torch
     import paper_2604_16734_amd as K
     from kvp_workload import chunk_ranges
@@ -95,7 +95,7 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
     elapsed = time.perf_counter() - t_begin
     ms_per_step = 1e3 * elapsed / steps
     proxy = None
-    if n_obs:
+    if n_obs and variants:
         # the paper's literal scoring (Sec. 3.2): n_obs proxy queries per layer, the same for every block
         gen = torch.Generator(device=device).manual_seed(1234)
         obs = [torch.randn((n_obs, wl.n_q_heads, wl.head_dim), generator=gen, device=device).to(torch.bfloat16)
@@ -107,14 +107,17 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         torch.cuda.synchronize()
         t_proxy = (time.perf_counter() - t_proxy) / steps
         proxy = {"n_obs": n_obs, "tokens_per_s": round(wl.n_tokens / t_proxy, 1), "ms_per_step": round(1e3 * t_proxy, 4)}
-    run_steps(driver, cache, wl, data, ranges, 1, outs, keydiff=True)
-    torch.cuda.synchronize()
-    t_kd = time.perf_counter()
-    run_steps(driver, cache, wl, data, ranges, steps, outs, keydiff=True)
-    torch.cuda.synchronize()
-    t_kd = (time.perf_counter() - t_kd) / steps
+    keydiff = None
+    if variants:
+        run_steps(driver, cache, wl, data, ranges, 1, outs, keydiff=True)
+        torch.cuda.synchronize()
+        t_kd = time.perf_counter()
+        run_steps(driver, cache, wl, data, ranges, steps, outs, keydiff=True)
+        torch.cuda.synchronize()
+        t_kd = (time.perf_counter() - t_kd) / steps
+        keydiff = {"tokens_per_s": round(wl.n_tokens / t_kd, 1), "ms_per_step": round(1e3 * t_kd, 4)}
     bulk = None
-    if wl.budget > wl.chunk and wl.budget + wl.budget <= 8192 and wl.n_tokens > wl.budget:
+    if variants and wl.budget > wl.chunk and wl.budget + wl.budget <= 8192 and wl.n_tokens > wl.budget:
         # hybrid execution (Sec. 4.3): the first `budget` tokens in one causal pass, then blocks
         bcache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.budget,
                          wl.segments, merge=True, scratch_sets=scratch_sets if two else 1, device=device)
@@ -131,44 +134,46 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         bulk = {"first_block": wl.budget, "tokens_per_s": round(wl.n_tokens / t_bulk, 1), "ms_per_step": round(1e3 * t_bulk, 4)}
         bcache.close()
         del bouts
-    # generation over the compressed caches (Eq. 1 with one query row): the attention of one new
-    # token in every layer, its own key and value being the whole tail
-    run_steps(driver, cache, wl, data, ranges, 1, outs)
-    torch.cuda.synchronize()
-    dq = [x[0][0].contiguous() for x in data]
-    dk = [x[1][:1].contiguous() for x in data]
-    dv = [x[2][:1].contiguous() for x in data]
-    dout = torch.empty_like(dq[0])
-    ptrs = [(dq[l].data_ptr(), dk[l].data_ptr(), dv[l].data_ptr()) for l in range(wl.n_layers)]
-    stream = torch.cuda.current_stream(device).cuda_stream
+    decode = None
+    if variants:
+        # generation over the compressed caches (Eq. 1 with one query row): the attention of one new
+        # token in every layer, its own key and value being the whole tail
+        run_steps(driver, cache, wl, data, ranges, 1, outs)
+        torch.cuda.synchronize()
+        dq = [x[0][0].contiguous() for x in data]
+        dk = [x[1][:1].contiguous() for x in data]
+        dv = [x[2][:1].contiguous() for x in data]
+        dout = torch.empty_like(dq[0])
+        ptrs = [(dq[l].data_ptr(), dk[l].data_ptr(), dv[l].data_ptr()) for l in range(wl.n_layers)]
+        stream = torch.cuda.current_stream(device).cuda_stream
 
-    def decode_tokens(count):
-        for _ in range(count):
-            for l, (pq, pk, pv) in enumerate(ptrs):
-                rc = K.kvp_decode_step(cache.handle, l, pq, pk, pv, 1, dout.data_ptr(), stream)
-                if rc:
-                    raise K.KvpError(rc, "kvp_decode_step")
-    decode_tokens(2)
-    torch.cuda.synchronize()
-    n_dec = 20
-    t_dec = time.perf_counter()
-    decode_tokens(n_dec)
-    torch.cuda.synchronize()
-    t_dec = (time.perf_counter() - t_dec) / n_dec
-    cache.profile_enable(True)
-    decode_tokens(2)
-    torch.cuda.synchronize()
-    dec_launches, dec_ms = cache.profile_read()["decode"]
-    cache.profile_enable(False)
-    kept = min(wl.budget, wl.n_tokens)
-    dec_bytes = 2 * wl.n_kv_heads * (kept + 1) * wl.head_dim * 2      # K and V rows of one layer, read once
-    decode = {"us_per_token_all_layers": round(1e6 * t_dec, 2), "us_per_layer_on_device": round(1e3 * dec_ms / dec_launches, 3),
-              "bytes_per_layer": dec_bytes, "GBps_on_device": round(dec_bytes / (1e-3 * dec_ms / dec_launches) / 1e9, 1),
-              "keys": kept + 1}
+        def decode_tokens(count):
+            for _ in range(count):
+                for l, (pq, pk, pv) in enumerate(ptrs):
+                    rc = K.kvp_decode_step(cache.handle, l, pq, pk, pv, 1, dout.data_ptr(), stream)
+                    if rc:
+                        raise K.KvpError(rc, "kvp_decode_step")
+        decode_tokens(2)
+        torch.cuda.synchronize()
+        n_dec = 20
+        t_dec = time.perf_counter()
+        decode_tokens(n_dec)
+        torch.cuda.synchronize()
+        t_dec = (time.perf_counter() - t_dec) / n_dec
+        cache.profile_enable(True)
+        decode_tokens(2)
+        torch.cuda.synchronize()
+        dec_launches, dec_ms = cache.profile_read()["decode"]
+        cache.profile_enable(False)
+        kept = min(wl.budget, wl.n_tokens)
+        dec_bytes = 2 * wl.n_kv_heads * (kept + 1) * wl.head_dim * 2      # K and V rows of one layer, read once
+        decode = {"us_per_token_all_layers": round(1e6 * t_dec, 2), "us_per_layer_on_device": round(1e3 * dec_ms / dec_launches, 3),
+                  "bytes_per_layer": dec_bytes, "GBps_on_device": round(dec_bytes / (1e-3 * dec_ms / dec_launches) / 1e9, 1),
+                  "keys": kept + 1}
     res = {
         "decode_step": decode,
         "bulk_first_pass": bulk,
-        "keydiff_scoring": {"tokens_per_s": round(wl.n_tokens / t_kd, 1), "ms_per_step": round(1e3 * t_kd, 4)},
+        "keydiff_scoring": keydiff,
         "proxy_scoring": proxy,
         "tokens_per_s": wl.n_tokens / (elapsed / steps),
         "ms_per_step": ms_per_step,
@@ -272,6 +277,8 @@ def main():
                          "once every (sets / 2) layers")
     ap.add_argument("--n-obs", type=int, default=64,
                     help="also time the prefill scored with this many proxy queries (0: skip)")
+    ap.add_argument("--variants", type=int, default=1,
+                    help="also time proxy-query and key-only scoring, the bulk first pass and the decode step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -296,14 +303,14 @@ def main():
         torch.cuda.synchronize()
         del a, b
     main_res = bench_workload(wl, args.steps, args.warmup, device, threads, streams=args.streams, n_obs=args.n_obs,
-                              scratch_sets=args.scratch_sets)
+                              scratch_sets=args.scratch_sets, variants=bool(args.variants))
 
     others = {}
     if args.others:
         for w in WORKLOADS:
             if w.name != wl.name:
                 r = bench_workload(w, max(3, args.steps // 2), 2, device, threads, profile=True, streams=args.streams,
-                                   scratch_sets=args.scratch_sets)
+                                   scratch_sets=args.scratch_sets, variants=False)
                 others[w.name] = {
                     "tokens_per_s": round(r["tokens_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4),
                     "attention_tflops": round(r["attention_tflops"], 2),
