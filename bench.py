@@ -73,7 +73,7 @@ def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None, keydiff=Fa
     driver.finish()
 
 
-def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=4, variants=True):
+def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=8, variants=True):
     import torch
     import paper_2604_16734_amd as K
     from kvp_workload import chunk_ranges
@@ -272,9 +272,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
                     help="2: kvp_compact of a layer runs on a second stream beside the next layers' kvp_prefill_chunk")
-    ap.add_argument("--scratch-sets", type=int, default=4,
-                    help="scratch sets of the cache with two streams: the main stream looks at the side stream "
-                         "once every (sets / 2) layers")
+    ap.add_argument("--scratch-sets", type=int, default=8,
+                    help="scratch sets of the cache with two streams: the layers go in groups of (sets / 2), "
+                         "two events between the streams per group")
     ap.add_argument("--n-obs", type=int, default=64,
                     help="also time the prefill scored with this many proxy queries (0: skip)")
     ap.add_argument("--variants", type=int, default=1,

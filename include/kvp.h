@@ -173,9 +173,15 @@ int kvp_compact(kvp_cache* cache, int32_t layer, const float* scores_override, v
  * attention reads the cache being compacted); the library orders the two
  * streams with its own events: a layer's next block waits for that layer's
  * compaction, and a scratch set waits for the compaction of the layer that
- * used it last.  That needs scratch_sets >= 2 (KVP_EINVAL otherwise).  Both
- * streams must have the default priority.  Errors as for the per-layer calls;
- * layers before the failing one have been enqueued and advanced. */
+ * used it last.  The layers go in groups of scratch_sets / 2 (attention and
+ * scoring of a group on `stream`, then its compactions on side_stream), so the
+ * streams exchange two events per group; the block's k and v of a layer are read
+ * by its compaction on side_stream and must stay valid until then.  That needs
+ * scratch_sets >= 2 (KVP_EINVAL otherwise).  Both streams must have the default
+ * priority, and between the first such call and kvp_free_cache the per-layer
+ * calls must not be mixed in on other streams (the library only orders what it
+ * enqueued here).  Errors as for the per-layer calls; layers before the failing
+ * one have been enqueued and advanced. */
 enum { KVP_SCORE_OWN = 0, KVP_SCORE_PROXY = 1, KVP_SCORE_KEYDIFF = 2 };
 int kvp_prefill_block(kvp_cache* cache, int32_t token_begin, int32_t n_tokens,
                       const void* const* q, const void* const* k, const void* const* v, void* const* out,

@@ -172,16 +172,27 @@ attention_kernel(const AttnArgs a) {
   // 64 banks (D = 128: a row spans all banks; D = 64: rows r and r + 2 share their banks)
   auto v_swizzle = [](int row) { return 4 * ((row % 4) >> (D == 64 ? 1 : 0)); };
   const int ld_chunk_v = ld_pos ^ v_swizzle(ld_row);
-  auto lds_dst = [&](u16* tile, int j) __attribute__((always_inline)) -> u16* {
-    return tile + (S::kRowGroup * j + S::kRowsPerLoad * wave) * D;     // wave-uniform
+  // LDS destination of instruction j into `tile`, as the byte address M0 wants: wave-uniform and
+  // all scalar arithmetic (the wave number is read into a scalar register once)
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned lds_base =
+      __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_raw);
+  auto lds_dst = [&](const u16* tile, int j) __attribute__((always_inline)) -> unsigned {
+    return lds_base + 2u * (unsigned)((int)(tile - lds_k) + (S::kRowGroup * j + S::kRowsPerLoad * wave_s) * D);
   };
   // Issued as inline assembly on purpose: the compiler then does not know that these loads write
   // LDS and does not make every later LDS read wait for them.  Ordering is this kernel's job:
   // wait_loads() before the barrier that publishes a tile.
-  auto load16 = [&](const u16* src, u16* dst) __attribute__((always_inline)) {
-    const unsigned lds_addr =
-        __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) void*)dst);
+  // Two address forms: a 64-bit address per lane (tiles that straddle the cache and the block or
+  // run past the end), and a scalar base with a 32-bit offset per lane (uniform tiles: the base
+  // moves from tile to tile on the scalar unit, the lane offsets never change).
+  auto load16 = [&](const u16* src, unsigned lds_addr) __attribute__((always_inline)) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr)
+                 : "m0", "memory");
+  };
+  auto load16_scalar_base = [&](const u16* base, unsigned lane_bytes, unsigned lds_addr) __attribute__((always_inline)) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_bytes), "s"(base),
+                 "s"(lds_addr)
                  : "m0", "memory");
   };
   auto wait_loads = [&]() __attribute__((always_inline)) {
@@ -192,15 +203,25 @@ attention_kernel(const AttnArgs a) {
     const int base = t * S::kTk;
     return base + S::kTk <= c || (base >= c && base + S::kTk <= n_cand);
   };
-  // one instruction (number j) of a uniform tile: src0 is this lane's address for j = 0
-  auto uniform_src = [&](const u16* cache, const u16* fresh, int t, int chunk, int& stride)
-      __attribute__((always_inline)) -> const u16* {
+  // A uniform tile: the scalar address of the first row this wave brings in, the row stride, and
+  // which of the lane offsets goes with it.  The lane part of an address is
+  // (ld_sub rows + the swizzled chunk) in bytes, one value per tensor and per stride.
+  struct UniformSrc {
+    const u16* base;
+    int stride;
+    bool cached;
+  };
+  auto uniform_src = [&](const u16* cache, const u16* fresh, int t) __attribute__((always_inline)) -> UniformSrc {
     const int base = t * S::kTk;
     const bool cached = base < c;
-    stride = cached ? D : new_stride;
-    return (cached ? cache + (size_t)base * D : fresh + (size_t)(base - c) * new_stride) + ld_row * stride +
-           8 * chunk;
+    const int stride = cached ? D : new_stride;
+    const u16* p = cached ? cache + (size_t)base * D : fresh + (size_t)(base - c) * new_stride;
+    return UniformSrc{p + (size_t)(S::kRowsPerLoad * wave_s) * stride, stride, cached};
   };
+  const unsigned lane_k_cache = 2u * (unsigned)(ld_sub * D + 8 * ld_chunk_k);
+  const unsigned lane_k_new = 2u * (unsigned)(ld_sub * new_stride + 8 * ld_chunk_k);
+  const unsigned lane_v_cache = 2u * (unsigned)(ld_sub * D + 8 * ld_chunk_v);
+  const unsigned lane_v_new = 2u * (unsigned)(ld_sub * new_stride + 8 * ld_chunk_v);
   auto issue_any_one = [&](const u16* cache, const u16* fresh, u16* tile, int t, int chunk, int j)
       __attribute__((always_inline)) {
     const int kv = min(t * S::kTk + S::kRowGroup * j + ld_row, n_cand - 1);   // past the end: any finite row
@@ -293,8 +314,9 @@ attention_kernel(const AttnArgs a) {
 
     // One phase, as one basic block: MFMA i is followed by the exponentials of 128 / D elements
     // of the S block computed in the previous phase, and LDS fragment reads run kAhead operands
-    // ahead of their use.  The scheduling-group barriers at the end ask the machine scheduler for
-    // exactly this interleaving.
+    // ahead of their use.  The source is written in exactly that order and a scheduling fence after
+    // every MFMA's share keeps the compiler from regrouping it (left to itself it bunches the
+    // MFMAs and piles the exponentials up behind them).
     //   s_exp -> p_out   P = exp2((S - m) * scale) for the block whose scores are ready
     //   s_new            S^T of the next block = K[kt rows] Q^T
     //   p_pend, vt       O^T += V^T P^T for the block exponentiated one phase ago
@@ -325,12 +347,16 @@ attention_kernel(const AttnArgs a) {
           const int t = ei / 16, r = ei % 16;
           const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s_exp[t][r], sl2, neg[t]));
           sum[t] += pe;
+          // the sums are only needed after the loop, and left alone the compiler gathers the
+          // additions of several phases in one place, keeping every exponential alive until then
+          asm volatile("" : "+v"(sum[t]));
           if (r & 1) p_out[t][r >> 1] = pack_bf16(held[t], pe); else held[t] = pe;
         }
       };
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int st = 0; st < kAhead; ++st) read_k(st);
+      __builtin_amdgcn_sched_barrier(0);     // all of them before the first MFMA
 #pragma unroll
       for (int st = 0; st < kNK; ++st) {
         if (st + kAhead < kNK) read_k(st + kAhead);
@@ -340,6 +366,7 @@ attention_kernel(const AttnArgs a) {
           s_new[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[st], qf[t][st], st == 0 ? zero : s_new[t], 0, 0, 0);
           exp_some();
           after_mfma(std::integral_constant<int, 0>{}, st * QT + t);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
 #pragma unroll
@@ -352,28 +379,11 @@ attention_kernel(const AttnArgs a) {
           o[t][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[vi], __builtin_bit_cast(bf16x8, pw), o[t][dt], 0, 0, 0);
           exp_some();
           after_mfma(std::integral_constant<int, 1>{}, vi * QT + t);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
 #pragma unroll
       for (int t = 0; t < QT; ++t) l_run[t] += sum[t];
-      // pipeline: the first kAhead operand reads, then per MFMA the read(s) of the operand kAhead
-      // further on (one 16-byte read for a K fragment, two transposing reads for a V^T fragment;
-      // an operand serves QT MFMAs) and the vector work of its elements
-      constexpr int kMfmas = QT * (kNK + kNV);
-      __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
-#pragma unroll
-      for (int i = 0; i < kMfmas; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
-        if (i % QT == 0) {
-          const int next = i / QT + kAhead;                                     // operand to fetch now
-          if (next < kNK) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          else if (next < kNK + kNV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        }
-        // per element: scale-and-shift, add to the row sum, half a pack to bf16; and the exponential
-        if (i & 1) __builtin_amdgcn_sched_group_barrier(0x002, (5 * kPerMfma + 1) / 2, 0);
-        else __builtin_amdgcn_sched_group_barrier(0x002, (5 * kPerMfma) / 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x400, kPerMfma, 0);
-      }
     };
 
     // ---- prologue: K(0), K(1), V(0) into LDS, S_X(0) computed
@@ -434,14 +444,17 @@ attention_kernel(const AttnArgs a) {
       constexpr int kEvery = kPerHalf / S::kLoadsPerWave;  // one load every kEvery MFMAs
       static_assert(kEvery >= 1 && kPerHalf % S::kLoadsPerWave == 0, "loads must fit the phase");
       if (kTag >= 0) {
-        int k_stride, v_stride;
-        const u16* k_src = uniform_src(kc, kn, t + 2, ld_chunk_k, k_stride);
-        const u16* v_src = uniform_src(vc, vn, t + 1, ld_chunk_v, v_stride);
+        const UniformSrc k_src = uniform_src(kc, kn, t + 2);
+        const UniformSrc v_src = uniform_src(vc, vn, t + 1);
+        const unsigned k_lane = k_src.cached ? lane_k_cache : lane_k_new;
+        const unsigned v_lane = v_src.cached ? lane_v_cache : lane_v_new;
         phase_core(sy, py, sx, k_nxt + blk_off, px, v_cur + blk_off, [&](auto half, int i) __attribute__((always_inline)) {
           if (i % kEvery != 0) return;
           const int j = i / kEvery;
-          if (decltype(half)::value == 0) load16(k_src + (size_t)(S::kRowGroup * j) * k_stride, lds_dst(k_cur, j));
-          else load16(v_src + (size_t)(S::kRowGroup * j) * v_stride, lds_dst(v_prv, j));
+          if (decltype(half)::value == 0)
+            load16_scalar_base(k_src.base + (size_t)(S::kRowGroup * j) * k_src.stride, k_lane, lds_dst(k_cur, j));
+          else
+            load16_scalar_base(v_src.base + (size_t)(S::kRowGroup * j) * v_src.stride, v_lane, lds_dst(v_prv, j));
         });
       } else {
         phase_core(sy, py, sx, k_nxt + blk_off, px, v_cur + blk_off, [&](auto half, int i) __attribute__((always_inline)) {

@@ -2,6 +2,7 @@
 // carving of the caller's device buffer, and kernel sequencing.  No device
 // memory is allocated and no stream is synchronised anywhere in this file
 // except kvp_profile_read, which waits for its own events.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -116,8 +117,13 @@ struct kvp_cache {
   bool profiling = false;
   std::vector<ProfEvent> events;      // recorded, not yet read
   std::vector<hipEvent_t> pool;       // idle events
-  // kvp_prefill_block: per layer, "attention and scoring enqueued" and "compaction enqueued"
+  // kvp_prefill_block with two streams works in groups of layers.  Per group, in a ring:
+  // "attention and scoring of the group enqueued" (main stream) and "its compactions
+  // enqueued" (side stream).  Groups are numbered from 0 for the life of the cache.
   std::vector<hipEvent_t> attended, compacted;
+  std::vector<long long> set_last_group;   // per scratch set: the last group that used it, or -1
+  long long n_groups = 0;                  // groups enqueued so far
+  long long waited_group = -1;             // the main stream already waits for groups up to this one
 
   u16* k_cache(int l) const { return reinterpret_cast<u16*>(base + lay.k_off + (size_t)l * lay.kv_layer_bytes); }
   u16* v_cache(int l) const { return reinterpret_cast<u16*>(base + lay.v_off + (size_t)l * lay.kv_layer_bytes); }
@@ -467,47 +473,71 @@ int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const
   const bool two = side_stream != nullptr && side_stream != stream && !c->dry;
   if (two && n_sets < 2) return KVP_EINVAL;      // compaction beside the next layer needs a second scratch set
   hipStream_t main = static_cast<hipStream_t>(stream), side = static_cast<hipStream_t>(side_stream);
-  // the main stream looks at the side stream once every `wait_every` layers
-  const int wait_every = n_sets >= 2 && n_sets <= n_layers ? n_sets / 2 : 1;
+  // With two streams the layers go in groups of half the scratch sets: the attention and
+  // scoring of a group on the main stream, one event, its compactions on the side stream, one
+  // event.  The streams so exchange two events per group instead of two per layer (a record
+  // costs the main stream about 4 us, a wait about 6 us), and while the side stream compacts
+  // one group the main stream has the other half of the sets for the next.
+  const int group = two ? std::max(1, n_sets / 2) : 1;
+  const size_t ring = (size_t)n_sets + 2;        // more than the groups any set can still refer to
   if (two && c->attended.empty()) {
     for (std::vector<hipEvent_t>* list : {&c->attended, &c->compacted})
-      for (int l = 0; l < n_layers; ++l) {
+      for (size_t i = 0; i < ring; ++i) {
         hipEvent_t e;
         if (hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice) != hipSuccess) return KVP_EDEVICE;
         list->push_back(e);
       }
+    c->set_last_group.assign(n_sets, -1);
   }
-  for (int layer = 0; layer < n_layers; ++layer) {
-    if (two && layer % wait_every == 0) {
-      // Scratch sets: layers [layer, layer + wait_every) reuse the sets of layers
-      // [layer - n_sets, layer - n_sets + wait_every), the last of which is layer - wait_every - 1
-      // (n_sets = 2 wait_every); the side stream is in order, so its compaction covers them all.
-      // The same wait covers the other hazard (a layer's cache must have taken its previous
-      // block): that compaction is earlier still on the side stream.  Before layer 0 the index
-      // wraps to the previous block's last layers.  An event never recorded holds nobody up.
-      const int dep = ((layer - wait_every - 1) % n_layers + n_layers) % n_layers;
-      if (hipStreamWaitEvent(main, c->compacted[dep], 0) != hipSuccess) return KVP_EDEVICE;
-    }
-    const int mode = scoring == KVP_SCORE_PROXY ? kScoreProxy : scoring == KVP_SCORE_KEYDIFF ? kScoreKeydiff : kScoreOwn;
-    int rc = prefill_impl(c, layer, token_begin, n_tokens, q[layer], k[layer], v[layer], out[layer],
-                          mode == kScoreProxy ? q_obs[layer] : nullptr, n_obs, mode, stream);
-    if (rc) return rc;
+  const int mode = scoring == KVP_SCORE_PROXY ? kScoreProxy : scoring == KVP_SCORE_KEYDIFF ? kScoreKeydiff : kScoreOwn;
+  for (int first = 0; first < n_layers; first += group) {
+    int last = std::min(n_layers, first + group);
     if (two) {
-      if (hipEventRecord(c->attended[layer], main) != hipSuccess) return KVP_EDEVICE;
-      if (hipStreamWaitEvent(side, c->attended[layer], 0) != hipSuccess) return KVP_EDEVICE;
+      // A scratch set must have been released by the compaction that used it last; the side
+      // stream is in order, so the latest such group covers the others, and with them the
+      // compaction of each layer's previous block (which used that layer's own set).
+      long long dep = -1;
+      for (int layer = first; layer < last; ++layer) dep = std::max(dep, c->set_last_group[layer % n_sets]);
+      if (dep > c->waited_group) {
+        if (hipStreamWaitEvent(main, c->compacted[dep % ring], 0) != hipSuccess) return KVP_EDEVICE;
+        c->waited_group = dep;
+      }
     }
-    rc = kvp_compact(c, layer, nullptr, two ? side_stream : stream);
+    int rc = KVP_OK;
+    for (int layer = first; layer < last; ++layer) {
+      rc = prefill_impl(c, layer, token_begin, n_tokens, q[layer], k[layer], v[layer], out[layer],
+                        mode == kScoreProxy ? q_obs[layer] : nullptr, n_obs, mode, stream);
+      if (rc) {
+        last = layer;                            // the layers before it still get their compaction
+        break;
+      }
+    }
+    const size_t slot = (size_t)(c->n_groups % ring);
+    if (two && last > first) {
+      if (hipEventRecord(c->attended[slot], main) != hipSuccess) return KVP_EDEVICE;
+      if (hipStreamWaitEvent(side, c->attended[slot], 0) != hipSuccess) return KVP_EDEVICE;
+    }
+    for (int layer = first; layer < last; ++layer) {
+      const int rc2 = kvp_compact(c, layer, nullptr, two ? side_stream : stream);
+      if (rc2) return rc2;
+    }
+    if (two && last > first) {
+      if (hipEventRecord(c->compacted[slot], side) != hipSuccess) return KVP_EDEVICE;
+      for (int layer = first; layer < last; ++layer) c->set_last_group[layer % n_sets] = c->n_groups;
+      ++c->n_groups;
+    }
     if (rc) return rc;
-    if (two && hipEventRecord(c->compacted[layer], side) != hipSuccess) return KVP_EDEVICE;
   }
   return KVP_OK;
 }
 
 int kvp_prefill_join(kvp_cache* c, void* stream, void* side_stream) {
   if (!c) return KVP_EINVAL;
-  if (c->dry || !side_stream || side_stream == stream || c->compacted.empty()) return KVP_OK;
-  for (hipEvent_t e : c->compacted)
-    if (hipStreamWaitEvent(static_cast<hipStream_t>(stream), e, 0) != hipSuccess) return KVP_EDEVICE;
+  if (c->dry || !side_stream || side_stream == stream || c->n_groups == 0) return KVP_OK;
+  // the side stream is in order: its last event covers every compaction before it
+  const size_t slot = (size_t)((c->n_groups - 1) % (long long)c->compacted.size());
+  if (hipStreamWaitEvent(static_cast<hipStream_t>(stream), c->compacted[slot], 0) != hipSuccess) return KVP_EDEVICE;
+  c->waited_group = c->n_groups - 1;
   return KVP_OK;
 }
 
