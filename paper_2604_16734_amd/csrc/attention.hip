@@ -327,30 +327,41 @@ attention_kernel(const AttnArgs a) {
       constexpr int kNV = (D / 32) * 2;      // V^T fragments
       constexpr int kAhead = D / 32;
       constexpr int kPerMfma = 128 / D;      // elements exponentiated per MFMA
-      float neg[QT], sum[QT], held[QT];
+      float neg[QT], sum[QT];
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
         const float m_use = (m_ref[t] == -INFINITY) ? 0.f : m_ref[t];   // row has seen nothing yet
         neg[t] = -m_use * sl2;
         sum[t] = 0.f;
-        held[t] = 0.f;
       }
       bf16x8 kfr[kNK], vfr[kNV];
       auto read_k = [&](int st) __attribute__((always_inline)) { kfr[st] = lds_read_b128(kt + k_off[st]); };
       auto read_v = [&](int vi) __attribute__((always_inline)) {
         vfr[vi] = lds_read_vt(vt + v_off[vi / 2] + 16 * (vi % 2) * D, 8 * D);
       };
+      // The vector work of an element is a chain (scale-and-shift, exponential, add to the row sum,
+      // pack) and an instruction that needs the result of the one before it stalls the wave, the
+      // exponential most of all.  So the chain is skewed over the MFMAs: each call computes the
+      // argument of the next element, the exponential of this one, and adds and packs the one before.
+      constexpr int kElems = QT * 16;
       int ei = 0;   // next element to exponentiate
+      float arg = __builtin_fmaf(s_exp[0][0], sl2, neg[0]), pe1 = 0.f, pe2 = 0.f;
+      auto finish_element = [&](int e) __attribute__((always_inline)) {      // element e: pe1, the one before: pe2
+        const int t = e / 16, r = e % 16;
+        sum[t] += pe1;
+        // the sums are only needed after the loop, and left alone the compiler gathers the
+        // additions of several phases in one place, keeping every exponential alive until then
+        asm volatile("" : "+v"(sum[t]));
+        if (r & 1) p_out[t][r >> 1] = pack_bf16(pe2, pe1);
+      };
       auto exp_some = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int k = 0; k < kPerMfma; ++k, ++ei) {
-          const int t = ei / 16, r = ei % 16;
-          const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s_exp[t][r], sl2, neg[t]));
-          sum[t] += pe;
-          // the sums are only needed after the loop, and left alone the compiler gathers the
-          // additions of several phases in one place, keeping every exponential alive until then
-          asm volatile("" : "+v"(sum[t]));
-          if (r & 1) p_out[t][r >> 1] = pack_bf16(held[t], pe); else held[t] = pe;
+          const float pe = __builtin_amdgcn_exp2f(arg);
+          if (ei + 1 < kElems) arg = __builtin_fmaf(s_exp[(ei + 1) / 16][(ei + 1) % 16], sl2, neg[(ei + 1) / 16]);
+          if (ei >= 1) finish_element(ei - 1);
+          pe2 = pe1;
+          pe1 = pe;
         }
       };
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -382,6 +393,7 @@ attention_kernel(const AttnArgs a) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+      finish_element(kElems - 1);
 #pragma unroll
       for (int t = 0; t < QT; ++t) l_run[t] += sum[t];
     };
@@ -444,8 +456,8 @@ attention_kernel(const AttnArgs a) {
       constexpr int kEvery = kPerHalf / S::kLoadsPerWave;  // one load every kEvery MFMAs
       static_assert(kEvery >= 1 && kPerHalf % S::kLoadsPerWave == 0, "loads must fit the phase");
       if (kTag >= 0) {
-        const UniformSrc k_src = uniform_src(kc, kn, t + 2);
-        const UniformSrc v_src = uniform_src(vc, vn, t + 1);
+        const UniformSrc k_src = uniform_src(kc, kn, t + 2 < n_tiles ? t + 2 : t);
+        const UniformSrc v_src = uniform_src(vc, vn, t + 1 < n_tiles ? t + 1 : t);
         const unsigned k_lane = k_src.cached ? lane_k_cache : lane_k_new;
         const unsigned v_lane = v_src.cached ? lane_v_cache : lane_v_new;
         phase_core(sy, py, sx, k_nxt + blk_off, px, v_cur + blk_off, [&](auto half, int i) __attribute__((always_inline)) {
@@ -468,16 +480,19 @@ attention_kernel(const AttnArgs a) {
     typedef std::integral_constant<int, 0> Even;
     typedef std::integral_constant<int, 1> Odd;
     typedef std::integral_constant<int, -1> Any;
-    // steady state: tiles t, t+1 plain and tiles t+1 .. t+3 uniform
-    int n_fast = 0;
-    while (n_fast + 1 < n_plain && tile_is_uniform(n_fast + 1) && tile_is_uniform(n_fast + 2) &&
-           tile_is_uniform(n_fast + 3))
-      n_fast += 2;
+    // The fast body of tile t needs: tile t visible in full to every row of the workgroup, and the
+    // tiles it prefetches (V of t + 1, K of t + 2) uniform, or past the workgroup's last tile (then
+    // it fetches its own tile again, into a buffer nobody reads any more).
+    auto fast_ok = [&](int t) __attribute__((always_inline)) -> bool {
+      return t < n_plain && tile_is_uniform(t + 1 < n_tiles ? t + 1 : t) && tile_is_uniform(t + 2 < n_tiles ? t + 2 : t);
+    };
+    int n_fast = 0;                // tiles the fast bodies take, two at a time
+    while (fast_ok(n_fast) && fast_ok(n_fast + 1)) n_fast += 2;
     int t = 0;
     if (n_fast >= 2) {
-      // tile 0 is plain: it gives every row its reference
+      // tile 0 is plain: it gives every row its reference, and nothing after it looks at maxima
       body(0, Even{}, std::false_type{}, std::true_type{});
-      body(1, Odd{}, std::false_type{}, std::true_type{});
+      body(1, Odd{}, std::false_type{}, std::false_type{});
       t = 2;
     }
     for (; t < n_fast; t += 2) {
