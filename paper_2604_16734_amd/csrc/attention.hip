@@ -140,20 +140,35 @@ attention_kernel(const AttnArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int qw = wave / KS;
-  const int ks = wave % KS;
+  // the same number in a scalar register: what a wave derives from it (its rows, its tile counts,
+  // its branches, addresses of its loads) is then uniform for the compiler as well
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int qw = wave_s / KS;
+  const int ks = wave_s % KS;
   const int l32 = lane & 31;
   const int g = lane >> 5;
 
   const int n = a.n, c = a.c, n_cand = c + a.n_keys, shift = a.shift;
-  const int row0 = rt * S::kRows;                    // first query row of the workgroup
-  const int q0 = row0 + qw * QT * 32;                // first query row of this wave
-  const int rows_end = min(n, row0 + S::kRows);
-  const int kv_end = min(n_cand, c + rows_end + shift);    // keys any row of the workgroup can see
-  const int n_tiles = (kv_end + S::kTk - 1) / S::kTk;
-  // tiles [0, n_plain) are visible in full to every row of the workgroup
-  const int n_plain = min(n_tiles, (min(c + row0 + shift + 1, n_cand)) / S::kTk);
-
+  // Rows.  A head's rows are cut into blocks of QT * 32 (one per group of KS waves); later rows
+  // see more of the block's keys.  A workgroup takes QW / 2 blocks from the front of the head
+  // and QW / 2 from the back, so every workgroup has the same amount of work; and since waves w
+  // and w + 4 of a workgroup share a SIMD, every SIMD of the eight-wave shape gets one early and
+  // one late block: when the early one has run out of visible keys the late one has the SIMD to
+  // itself.  first_row_of(q) is the first row of the block the waves with qw = q work on.
+  auto first_row_of = [&](int q) __attribute__((always_inline)) -> int {
+    constexpr int kHalf = QW / 2;
+    const int blocks = a.n_row_tiles * QW;
+    const int b = q < kHalf ? rt * kHalf + q : blocks - (rt + 1) * kHalf + (q - kHalf);
+    return b * QT * 32;
+  };
+  const int q0 = first_row_of(qw);                   // first query row of this wave
+  // the workgroup as a whole: the last block is the latest; tiles are staged for everybody
+  const int wg_rows_end = min(n, first_row_of(QW - 1) + QT * 32);
+  const int n_tiles = (min(n_cand, c + wg_rows_end + shift) + S::kTk - 1) / S::kTk;
+  // this wave: the tiles its rows can see, and those among them visible in full to all its rows
+  const int my_rows_end = min(n, q0 + QT * 32);      // = n for a block that lies past the end: computed, not stored
+  const int my_tiles = (min(n_cand, c + my_rows_end + shift) + S::kTk - 1) / S::kTk;
+  const int n_plain = min(my_tiles, (min(c + q0 + shift + 1, n_cand)) / S::kTk);
   const u16* kc = a.k_cache + (size_t)hk * a.budget * D;
   const u16* vc = a.v_cache + (size_t)hk * a.budget * D;
   const u16* kn = a.k_new + (size_t)hk * D;
@@ -174,7 +189,6 @@ attention_kernel(const AttnArgs a) {
   const int ld_chunk_v = ld_pos ^ v_swizzle(ld_row);
   // LDS destination of instruction j into `tile`, as the byte address M0 wants: wave-uniform and
   // all scalar arithmetic (the wave number is read into a scalar register once)
-  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const unsigned lds_base =
       __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_raw);
   auto lds_dst = [&](const u16* tile, int j) __attribute__((always_inline)) -> unsigned {
@@ -499,13 +513,13 @@ attention_kernel(const AttnArgs a) {
       body(t, Even{}, std::false_type{}, std::false_type{});
       body(t + 1, Odd{}, std::false_type{}, std::false_type{});
     }
-    for (; t < n_tiles; ++t)       // masking a fully visible tile is harmless
+    for (; t < my_tiles; ++t)      // masking a fully visible tile is harmless
       body(t, Any{}, std::true_type{}, std::true_type{});
-    wait_loads();
-    __syncthreads();               // V of the last tile has landed for everybody
     {
-      // O += P_Y V of the last tile
-      const u16* vt = lds_v + ((n_tiles + 1) & 1) * S::kTile + blk_off + 32 * D;
+      // O += P_Y V of this wave's last tile.  That V was published by the barrier inside the last
+      // body and is overwritten only after the barrier of the next tile, which this wave has
+      // not reached.
+      const u16* vt = lds_v + ((my_tiles + 1) & 1) * S::kTile + blk_off + 32 * D;
 #pragma unroll
       for (int vi = 0; vi < (D / 32) * 2; ++vi) {
         const int dt = vi / 2, mm = vi % 2;
@@ -517,6 +531,16 @@ attention_kernel(const AttnArgs a) {
         }
       }
     }
+    // The workgroup's later tiles, which no row of this wave sees: keep in step with the others
+    // (one barrier per tile) and bring in this wave's share of the tiles they read.
+    for (; t < n_tiles; ++t) {
+      wait_loads();
+      __syncthreads();
+      issue_any(kc, kn, lds_k + (t & 1) * S::kTile, t + 2, ld_chunk_k);
+      issue_any(vc, vn, lds_v + ((t & 1) ^ 1) * S::kTile, t + 1, ld_chunk_v);
+    }
+    wait_loads();
+    __syncthreads();               // nothing is on its way into LDS any more
     // a logit more than 2^64 above its row's reference in a tile that did not track maxima has
     // pushed the row sum past 2^64 (or to infinity or NaN)
 #pragma unroll
@@ -615,7 +639,7 @@ attention_kernel(const AttnArgs a) {
   // Only reached when a logit exceeded its row's reference by more than 2^64.
   {
     const bool active = wave < S::kRows / 32;
-    const int qs = row0 + 32 * wave;
+    const int qs = active ? first_row_of(wave / QT) + 32 * (wave % QT) : 0;
     bf16x8 qf[D / 16];
     {
       const int row = min(qs + l32, n - 1);
