@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, vendor figure
 # HBM bytes per attention launch (fetch + write) at the long_video steady state, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (launch-weighted mean,
 # counters scaled by what they read for a plain 256 MiB copy); None for a workload not measured
-ATTENTION_TRAFFIC_BYTES = {"long_video": 28214990}
+ATTENTION_TRAFFIC_BYTES = {"long_video": 28214600}
 
 
 def attention_flops(wl, t0_n_pairs):
@@ -284,7 +284,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (no collectives, "
-              "nothing to shard: see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "nothing to shard: budget, scores and eviction are per layer and KV head)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
