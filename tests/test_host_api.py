@@ -179,6 +179,46 @@ def test_decode_step_state_machine():
         K.kvp_free_cache(h)
 
 
+def test_prefill_block_walks_every_layer():
+    """kvp_prefill_block in a dry run (no device work, so everything on one stream): every layer
+    advances by the block, errors are reported before any layer moves, and a per-layer call that
+    leaves a layer pending makes the block call stop at that layer with the earlier ones done."""
+    wl = get_workload("tiled_image")
+    rc, h = K.kvp_init_cache(_cfg(wl, sets=wl.n_layers), wl.segments, None, 0)    # a scratch set per layer
+    assert rc == K.KVP_OK
+    zeros = [0] * wl.n_layers
+    try:
+        assert K.kvp_prefill_block(h, 0, wl.chunk + 1, zeros, zeros, zeros, zeros) == K.KVP_EINVAL
+        assert K.kvp_prefill_block(h, 5, 8, zeros, zeros, zeros, zeros) == K.KVP_ESTATE          # tokens skipped
+        assert K.kvp_prefill_block(h, 0, 8, zeros, zeros, zeros, zeros, scoring=7) == K.KVP_EINVAL
+        assert K.kvp_prefill_block(h, 0, 8, zeros, zeros, zeros, zeros, scoring=K.KVP_SCORE_PROXY) == K.KVP_EINVAL  # no proxy queries
+        for layer in range(wl.n_layers):
+            rc, vw = K.kvp_decode_ready(h, layer)
+            assert rc == K.KVP_OK and (vw.count, vw.next_token) == (0, 0)
+        t = 0
+        for n, scoring in ((wl.chunk, K.KVP_SCORE_OWN), (wl.chunk, K.KVP_SCORE_KEYDIFF), (40, K.KVP_SCORE_PROXY)):
+            obs = zeros if scoring == K.KVP_SCORE_PROXY else None
+            assert K.kvp_prefill_block(h, t, n, zeros, zeros, zeros, zeros, scoring=scoring, q_obs=obs, n_obs=4) == K.KVP_OK
+            t += n
+            for layer in range(wl.n_layers):
+                rc, vw = K.kvp_decode_ready(h, layer)
+                assert rc == K.KVP_OK and (vw.count, vw.next_token) == (min(wl.budget, t), t)
+        assert K.kvp_prefill_join(h) == K.KVP_OK
+        # layer 3 taken out of step by a per-layer call: the block call does layers 0-2 and stops there
+        assert K.kvp_prefill_chunk(h, 3, t, 8, 0, 0, 0, 0) == K.KVP_OK
+        assert K.kvp_prefill_block(h, t, 8, zeros, zeros, zeros, zeros) == K.KVP_ESTATE
+        for layer in range(wl.n_layers):
+            rc, vw = K.kvp_decode_ready(h, layer)
+            if layer < 3:
+                assert rc == K.KVP_OK and vw.next_token == t + 8
+            elif layer == 3:
+                assert rc == K.KVP_ESTATE
+            else:
+                assert rc == K.KVP_OK and vw.next_token == t
+    finally:
+        K.kvp_free_cache(h)
+
+
 def test_scratch_sets_gate_pending_layers():
     wl = get_workload("single_image")
     for sets, second_ok in ((1, False), (2, True)):
