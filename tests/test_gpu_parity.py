@@ -464,11 +464,14 @@ def test_free_running_invariants(name):
         assert np.array_equal(results[0][layer][1], results[1][layer][1])
 
 
-@pytest.mark.parametrize("name,sets", [("tiled_image", 2), ("video", 2), ("tiled_image", 3), ("video", 4), ("tiled_image", 6),
-                                       ("video", 5), ("video", 8), ("tiled_image", 7)])
-def test_compaction_on_a_second_stream_changes_nothing(name, sets):
-    """The whole prefill with every kvp_compact on a second stream (two scratch sets, events
-    between the streams) must leave bit for bit the caches and outputs of the in-order run."""
+@pytest.mark.parametrize("name,sets,scoring", [
+    ("tiled_image", 2, "own"), ("video", 2, "own"), ("tiled_image", 3, "own"), ("video", 4, "own"), ("tiled_image", 6, "own"),
+    ("video", 5, "own"), ("video", 8, "own"), ("tiled_image", 7, "own"),
+    ("tiled_image", 4, "proxy"), ("video", 8, "proxy"), ("tiled_image", 4, "keydiff"), ("video", 6, "keydiff")])
+def test_compaction_on_a_second_stream_changes_nothing(name, sets, scoring):
+    """The whole prefill with every kvp_compact on a second stream (events between the streams, one
+    pair per group of layers) must leave bit for bit the caches and outputs of the in-order run,
+    whichever way the candidates are scored."""
     wl = get_workload(name)
     layers = min(wl.n_layers, max(6, sets))      # groups of sets / 2 layers; 5 and 7 make the set use irregular
     data = [tuple(U.bits_to_torch(x) for x in layer_inputs(wl, l)) for l in range(layers)]
@@ -480,8 +483,14 @@ def test_compaction_on_a_second_stream_changes_nothing(name, sets):
         driver = K.Prefill(cache, layers, overlap=overlap)
         outs = [torch.zeros((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=DEV)
                 for _ in range(layers)]
+        obs = None
+        if scoring == "proxy":
+            gen = torch.Generator(device=DEV).manual_seed(99)
+            obs = [torch.randn((24, wl.n_q_heads, wl.head_dim), generator=gen, device=DEV).to(torch.bfloat16)
+                   for _ in range(layers)]
         for t0, n in ranges:
-            driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n])
+            driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n],
+                         (lambda l: obs[l]) if obs is not None else None, scoring == "keydiff")
         driver.finish()
         torch.cuda.synchronize()
         state = []
