@@ -467,7 +467,8 @@ def test_free_running_invariants(name):
 @pytest.mark.parametrize("name,sets,scoring", [
     ("tiled_image", 2, "own"), ("video", 2, "own"), ("tiled_image", 3, "own"), ("video", 4, "own"), ("tiled_image", 6, "own"),
     ("video", 5, "own"), ("video", 8, "own"), ("tiled_image", 7, "own"),
-    ("tiled_image", 4, "proxy"), ("video", 8, "proxy"), ("tiled_image", 4, "keydiff"), ("video", 6, "keydiff")])
+    ("tiled_image", 4, "proxy"), ("video", 8, "proxy"), ("tiled_image", 4, "keydiff"), ("video", 6, "keydiff"),
+    ("long_video", 8, "own")])                      # the benchmark's shape and scratch sets, eight of its layers
 def test_compaction_on_a_second_stream_changes_nothing(name, sets, scoring):
     """The whole prefill with every kvp_compact on a second stream (events between the streams, one
     pair per group of layers) must leave bit for bit the caches and outputs of the in-order run,
