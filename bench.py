@@ -45,8 +45,7 @@ def attention_flops(wl, t0_n_pairs):
 
 def generate(wl, device, threads):
     import torch
-    from kvp_workload import layer_inputs
-    from tests.gpu_util import bits_to_torch
+    from kvp_workload import layer_inputs, bits_to_torch
 
     def one(layer):
         return layer_inputs(wl, layer)

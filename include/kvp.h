@@ -32,10 +32,8 @@
  *    and token ranges are consecutive from 0.  A layer is PENDING between
  *    its prefill_chunk and its compact, READY otherwise.
  *  - A kvp_cache is not thread-safe; use one host thread per cache.
- *  - Tuning aid: the environment variable KVP_ATTN_VARIANT (0, 1 or 2), read at
- *    every kvp_prefill_chunk, forces one of the attention kernel's workgroup
- *    shapes instead of the one chosen from the launch size.  Results are the
- *    same to rounding; only speed differs.
+ *  - The library reads no environment variable and keeps no global state that
+ *    changes results: everything it is told comes through these calls.
  */
 #ifndef KVP_H
 #define KVP_H
@@ -226,6 +224,13 @@ int kvp_decode_step(kvp_cache* cache, int32_t layer, const void* q, const void* 
  * into the layer's K, V, token_idx and weight (through the kvp_view pointers)
  * and that the next block starts at `next_token`.  Layer becomes READY. */
 int kvp_set_state(kvp_cache* cache, int32_t layer, int32_t count, int32_t next_token);
+
+/* Tuning and test aid: force one of the attention kernel's three workgroup shapes
+ * for every later kvp_prefill_chunk of this cache (0: four waves of 64 rows,
+ * 1: four waves of 32 rows, 2: eight waves of 32 rows), or -1 to let the library
+ * choose from the launch size again (the default).  Results are the same to
+ * rounding; only speed differs.  KVP_EINVAL for any other value. */
+int kvp_set_attention_shape(kvp_cache* cache, int32_t shape);
 
 /* Inspection of the last block of a layer (device pointers, valid until the
  * layer's scratch set is reused).  n_cand = c + n of that block; candidates are

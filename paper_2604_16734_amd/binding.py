@@ -99,6 +99,8 @@ def lib():
         L.kvp_decode_ready.argtypes = [vp, i32, P(KvpView)]
         L.kvp_set_state.restype = ctypes.c_int
         L.kvp_set_state.argtypes = [vp, i32, i32, i32]
+        L.kvp_set_attention_shape.restype = ctypes.c_int
+        L.kvp_set_attention_shape.argtypes = [vp, i32]
         L.kvp_debug_last.restype = ctypes.c_int
         L.kvp_debug_last.argtypes = [vp, i32, P(vp), P(vp), P(vp), P(i32), P(i32)]
         L.kvp_profile_enable.restype = ctypes.c_int
@@ -197,6 +199,10 @@ def kvp_set_state(handle, layer, count, next_token):
     return lib().kvp_set_state(handle, layer, count, next_token)
 
 
+def kvp_set_attention_shape(handle, shape):
+    return lib().kvp_set_attention_shape(handle, shape)
+
+
 def kvp_debug_last(handle, layer):
     """Returns (code, scores_ptr, keep_ptr, dst_ptr, n_cand, stride)."""
     s, k, d = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
@@ -233,8 +239,13 @@ class Cache:
     Tensors must be contiguous bfloat16 on the cache's device.  Every method is
     argument marshalling around one C call."""
 
+    # bytes of guard band on either side of the device buffer of every Cache created from now on
+    # (tests set it; see guards_intact)
+    default_guard_bytes = 0
+
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, budget, chunk_max, segments,
-                 merge=False, scratch_sets=1, softmax_scale=0.0, device="cuda:0", stream=None):
+                 merge=False, scratch_sets=1, softmax_scale=0.0, device="cuda:0", stream=None,
+                 guard_bytes=None):
         import torch
         self.torch = torch
         self.cfg = KvpConfig(n_layers, n_q_heads, n_kv_heads, head_dim, budget, chunk_max,
@@ -246,10 +257,29 @@ class Cache:
         self.device = torch.device(device)
         self.nbytes = nbytes
         self.persistent_bytes = kvp_persistent_bytes(self.cfg)
-        self.buf = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
-        self._base = (self.buf.data_ptr() + 255) // 256 * 256
+        # Optional guard bands: the whole allocation is filled with 0xFF (a NaN pattern in bf16 and
+        # fp32, -1 as a token index) before the library gets the part in the middle, so that a
+        # write outside that part shows up in guards_intact() and a read of a never-written slot
+        # shows up as NaN in the results.
+        self.guard = Cache.default_guard_bytes if guard_bytes is None else int(guard_bytes)
+        assert self.guard >= 0 and self.guard % 256 == 0
+        self.buf = torch.empty(nbytes + 256 + 2 * self.guard, dtype=torch.uint8, device=self.device)
+        if self.guard:
+            self.buf.fill_(0xFF)
+            if stream is not None:      # the fill ran on torch's current stream, the library may use another
+                torch.cuda.current_stream(self.device).synchronize()
+        self._base = (self.buf.data_ptr() + self.guard + 255) // 256 * 256
         rc, self.handle = kvp_init_cache(self.cfg, self.segments, self._base, nbytes, self._stream(stream))
         _check(rc, "kvp_init_cache")
+
+    def guards_intact(self):
+        """True when no byte outside the part handed to the library has changed since creation
+        (always True for a cache created without guard bands)."""
+        if not self.guard:
+            return True
+        lo = self._base - self.buf.data_ptr()
+        hi = lo + self.nbytes
+        return bool((self.buf[:lo] == 0xFF).all()) and bool((self.buf[hi:] == 0xFF).all())
 
     def _stream(self, stream=None):
         if stream is None:
@@ -346,6 +376,9 @@ class Cache:
 
     def set_state(self, layer, count, next_token):
         _check(kvp_set_state(self.handle, layer, count, next_token), "kvp_set_state")
+
+    def set_attention_shape(self, shape):
+        _check(kvp_set_attention_shape(self.handle, shape), "kvp_set_attention_shape")
 
     def debug_last(self, layer):
         """(scores, keep, dst) of the layer's last block, each [Hkv, n_cand]."""

@@ -52,7 +52,6 @@
 // overflow near 2^127) the workgroup raises a flag, throws its result away and
 // redoes its rows with the textbook online softmax in a plain loop.  Real
 // attention logits never get there; adversarial inputs stay correct.
-#include <cstdlib>
 #include <type_traits>
 
 #include "kvp_internal.h"
@@ -732,32 +731,39 @@ attention_kernel(const AttnArgs a) {
 template <int D, int QT, int QW, int KS>
 hipError_t launch_shape(const AttnArgs& a, hipStream_t s) {
   using S = Shape<D, QT, QW, KS>;
-  auto kern = attention_kernel<D, QT, QW, KS>;
-  static bool attr_done = false;   // per process; the attribute belongs to the function
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
   const int grid = kXcds * a.work_per_xcd;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(S::kThreads), S::kLdsBytes, s, a);
+  hipLaunchKernelGGL((attention_kernel<D, QT, QW, KS>), dim3(grid), dim3(S::kThreads), S::kLdsBytes, s, a);
   return hipGetLastError();
+}
+
+template <int D, int QT, int QW, int KS>
+hipError_t prepare_shape() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(attention_kernel<D, QT, QW, KS>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, Shape<D, QT, QW, KS>::kLdsBytes);
 }
 
 constexpr int kRowsOfVariant[3] = {128, 64, 128};
 
 }  // namespace
 
-void plan_attention(AttnArgs& a, int /*head_dim*/) {
+// Every shape needs more dynamic LDS than a kernel gets by default.  The attribute belongs to the
+// function on the current device, so this runs once per cache creation, on the cache's device.
+hipError_t prepare_attention() {
+  hipError_t e;
+  if ((e = prepare_shape<128, 2, 2, 2>()) != hipSuccess) return e;
+  if ((e = prepare_shape<128, 1, 4, 2>()) != hipSuccess) return e;
+  if ((e = prepare_shape<128, 1, 2, 2>()) != hipSuccess) return e;
+  if ((e = prepare_shape<64, 2, 2, 2>()) != hipSuccess) return e;
+  if ((e = prepare_shape<64, 1, 4, 2>()) != hipSuccess) return e;
+  return prepare_shape<64, 1, 2, 2>();
+}
+
+void plan_attention(AttnArgs& a, int /*head_dim*/, int forced_shape) {
   auto wgs = [&](int rows) { return ((a.n + rows - 1) / rows) * a.n_q_heads; };
   // eight waves x 32 rows (two waves per SIMD) when 128-row workgroups fill the chip,
   // otherwise four waves x 32 rows over 64-row workgroups
   a.variant = wgs(128) >= 192 ? 2 : 1;
-  if (const char* e = getenv("KVP_ATTN_VARIANT")) {                      // tuning aid: 0, 1 or 2
-    const int v = atoi(e);
-    if (v >= 0 && v <= 2) a.variant = v;
-  }
+  if (forced_shape >= 0 && forced_shape <= 2) a.variant = forced_shape;      // kvp_set_attention_shape
   const int rows = kRowsOfVariant[a.variant];
   a.n_row_tiles = (a.n + rows - 1) / rows;
   a.total_work = a.n_row_tiles * a.n_q_heads;

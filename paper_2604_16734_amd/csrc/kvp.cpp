@@ -114,6 +114,7 @@ struct kvp_cache {
   std::vector<int> set_owner;         // layer holding each scratch set, or -1
   float scale;
   bool dry;
+  int attn_shape = -1;                // kvp_set_attention_shape; < 0: chosen per launch
   bool profiling = false;
   std::vector<ProfEvent> events;      // recorded, not yet read
   std::vector<hipEvent_t> pool;       // idle events
@@ -309,8 +310,11 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
   c->set_owner.assign(lay.n_sets, -1);
   if (!dry) {
     const size_t slots = (size_t)cfg->n_layers * lay.meta_layer_elems;
-    hipError_t e = launch_init(c->idx(0), c->weight(0), slots, c->segs.data(), n_segs, c->dev_segs(),
-                               static_cast<hipStream_t>(stream));
+    hipError_t e = prepare_attention();
+    if (e == hipSuccess) e = prepare_select();
+    if (e == hipSuccess)
+      e = launch_init(c->idx(0), c->weight(0), slots, c->segs.data(), n_segs, c->dev_segs(),
+                      static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
       delete c;
       return KVP_EDEVICE;
@@ -359,7 +363,7 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
   aa.n_q_heads = cfg.n_q_heads; aa.n_kv_heads = cfg.n_kv_heads;
   aa.budget = cfg.budget; aa.lse_stride = cfg.chunk_max;
   aa.scale_log2 = c->scale * 1.4426950408889634f;
-  plan_attention(aa, cfg.head_dim);
+  plan_attention(aa, cfg.head_dim, c->attn_shape);
   int rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
   if (rc) return rc;
 
@@ -389,7 +393,7 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
         ra.scale_log2 = aa.scale_log2;
         rc = launch(c, KVP_K_ROWSTAT, s, [&] { return launch_rowstat(ra, cfg.head_dim, s); });
       } else {
-        plan_attention(aa, cfg.head_dim);
+        plan_attention(aa, cfg.head_dim, c->attn_shape);
         rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
       }
       if (rc) return rc;
@@ -595,6 +599,12 @@ int kvp_set_state(kvp_cache* c, int32_t layer, int32_t count, int32_t next_token
   L.count = count;
   L.next_token = next_token;
   L.has_last = false;
+  return KVP_OK;
+}
+
+int kvp_set_attention_shape(kvp_cache* c, int32_t shape) {
+  if (!c || shape < -1 || shape > 2) return KVP_EINVAL;
+  c->attn_shape = shape;
   return KVP_OK;
 }
 

@@ -164,7 +164,9 @@ hipError_t launch_init(int32_t* token_idx, float* weight, size_t n_slots, const 
 int rows_per_compact_block();
 
 // host-side planning shared by launchers and the state machine
-void plan_attention(AttnArgs& a, int head_dim);
+void plan_attention(AttnArgs& a, int head_dim, int forced_shape);   // forced_shape < 0: chosen from the launch size
+hipError_t prepare_attention();   // function attributes on the current device; once per cache creation
+hipError_t prepare_select();
 void plan_colsum(ColsumArgs& a, int head_dim);
 int colsum_max_partials(int group, int chunk_max);
 size_t select_lds_bytes(int n_cand, int items, int table_size);

@@ -522,18 +522,25 @@ size_t select_lds_bytes(int /*n_cand*/, int items, int table_size) {
 
 hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s) {
   const size_t lds = select_lds_bytes(a.c + a.n, a.items, a.table_size);
-  const bool small = a.items <= 4;
-  const void* fn = small ? reinterpret_cast<const void*>(select_kernel<4>)
-                         : reinterpret_cast<const void*>(select_kernel<kMaxItemsAny>);
-  static size_t attr_bytes[2] = {0, 0};
-  if (lds > attr_bytes[small]) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_bytes[small] = lds;
-  }
-  if (small) hipLaunchKernelGGL(select_kernel<4>, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
+  if (a.items <= 4) hipLaunchKernelGGL(select_kernel<4>, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
   else hipLaunchKernelGGL(select_kernel<kMaxItemsAny>, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
   return hipGetLastError();
+}
+
+// Allows both kernels the dynamic LDS of the largest head they can be given (the attribute
+// belongs to the function on the current device: called at cache creation).
+hipError_t prepare_select() {
+  const int sizes[2] = {4, kMaxItemsAny};
+  const void* fns[2] = {reinterpret_cast<const void*>(select_kernel<4>),
+                        reinterpret_cast<const void*>(select_kernel<kMaxItemsAny>)};
+  for (int i = 0; i < 2; ++i) {
+    int ts = 2;
+    while (ts < 2 * sizes[i] * kThreads) ts <<= 1;
+    const size_t lds = select_lds_bytes(sizes[i] * kThreads, sizes[i], ts);
+    hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace kvp

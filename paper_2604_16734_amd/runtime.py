@@ -64,6 +64,12 @@ class Prefill:
         rc = B.kvp_prefill_block(cache.handle, t0, n, ptr(qs), ptr(ks), ptr(vs), ptr(outs), scoring,
                                  ptr(obs) if obs else None, obs[0].shape[0] if obs else 0, main, side)
         B._check(rc, "kvp_prefill_block")
+        if self.side is not None:
+            # the compactions just enqueued on the side stream read the block's K and V after this
+            # call returns: tell torch's allocator, so that memory the caller drops now is not
+            # handed out again before the side stream is done with it
+            for t in ks + vs:
+                t.record_stream(self.side)
         return outs
 
     def finish(self):

@@ -17,6 +17,10 @@ from tests import gpu_util as U
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+# Free-running comparison (nothing re-synchronised): floors below what the three small workloads
+# give, so that they flag a real divergence and not a near-tie decided the other way.
+FREE_RUNNING_JACCARD_FLOOR = 0.9
+FREE_RUNNING_OUT_TOL = 5e-2
 
 
 def _rand_bits(rng, shape, scale=1.0):
@@ -24,12 +28,15 @@ def _rand_bits(rng, shape, scale=1.0):
     return f32_to_bf16_bits((scale * rng.standard_normal(shape)).astype(np.float32))
 
 
-def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0, n_obs=0, keydiff=False):
+def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0, n_obs=0, keydiff=False,
+                    attention_shape=None):
     """One prefill_chunk (or prefill_chunk_proxy with n_obs proxy queries) on a cache preloaded
     with c random entries."""
     rng = np.random.default_rng(seed)
     segs = [Segment(0, 100000, 0)]
     cache = K.Cache(1, hq, hkv, d, budget, chunk_max, segs, merge=False, softmax_scale=scale, device=DEV)
+    if attention_shape is not None:
+        cache.set_attention_shape(attention_shape)
     oc = O.LayerCache(hkv, d, budget)
     if c:
         kb0, vb0 = _rand_bits(rng, (c, hkv, d)), _rand_bits(rng, (c, hkv, d))
@@ -69,22 +76,39 @@ def _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed, scale=0.0, n_obs=
     (32, 8, 128, 640, 1024, 4096, 1024),  # rows-128 variant, diagonal over many tiles
     (28, 4, 128, 300, 512, 4096, 512),  # group of 7
 ])
-def test_attention_and_scores(hq, hkv, d, c, n, budget, chunk_max):
+def test_attention_outputs(hq, hkv, d, c, n, budget, chunk_max):
+    """Eq. 1 alone: c + n <= budget in every case here, so nothing is scored or evicted and the
+    block is appended.  Scores are checked where an eviction makes the library form them
+    (test_scores_and_free_selection and every lock-step test)."""
     cache, oc, err, scores_ref, _ = _attention_case(hq, hkv, d, c, n, budget, chunk_max, seed=c + n)
     assert err <= U.OUT_TOL, err
-    # c + n <= budget here, so compact appended everything; the scores stay in scratch only
-    # when a selection ran.  Read them through a second call that does select: see below.
+    k, v, idx, w, count, nxt = cache.decode_ready(0)
+    assert count == c + n and nxt == c + n
+    assert np.array_equal(idx[:, c:count].cpu().numpy(), np.broadcast_to(np.arange(c, c + n), (hkv, n)))
     cache.close()
 
 
 @pytest.mark.parametrize("variant", [0, 1, 2])
 @pytest.mark.parametrize("hq,hkv,d,c,n", [(8, 2, 128, 193, 300), (4, 4, 64, 70, 200), (4, 2, 128, 0, 129)])
-def test_every_workgroup_shape(monkeypatch, variant, hq, hkv, d, c, n):
-    # the library picks the attention workgroup shape from the launch size; the tuning
-    # variable forces each compiled shape in turn so that none goes untested
-    monkeypatch.setenv("KVP_ATTN_VARIANT", str(variant))
-    cache, oc, err, scores_ref, _ = _attention_case(hq, hkv, d, c, n, 4096, 512, seed=7 * c + n + variant)
+def test_every_workgroup_shape(variant, hq, hkv, d, c, n):
+    # the library picks the attention workgroup shape from the launch size; the tuning call
+    # forces each compiled shape in turn so that none goes untested
+    cache, oc, err, scores_ref, _ = _attention_case(hq, hkv, d, c, n, 4096, 512, seed=7 * c + n + variant,
+                                                    attention_shape=variant)
     assert err <= U.OUT_TOL, err
+    cache.close()
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_every_workgroup_shape_scores(variant):
+    """Each workgroup shape leaves the row statistics the scoring pass reads: scores and the
+    selection made from them, with the shape forced."""
+    hq, hkv, d, c, n, budget = 8, 2, 128, 300, 200, 300
+    cache, oc, err, scores_ref, _ = _attention_case(hq, hkv, d, c, n, budget, 256, seed=11 + variant,
+                                                    attention_shape=variant)
+    assert err <= U.OUT_TOL, err
+    scores_gpu, keep, dst = cache.debug_last(0)
+    U.check_scores(scores_gpu.cpu().numpy(), scores_ref, n * (hq // hkv))
     cache.close()
 
 
@@ -245,7 +269,7 @@ def test_decode_step_after_prefill():
     wl = get_workload("tiled_image")
     cache = K.Cache(1, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments, merge=True, device=DEV)
     qb, kb, vb = layer_inputs(wl, 0)
-    oc = U.lockstep_layer(wl, 0, cache, qb, kb, vb, True)
+    oc = U.lockstep_layer(wl, 0, cache, qb, kb, vb, True, own_scores=False)
     rng = np.random.default_rng(5)
     hq, hkv, d = wl.n_q_heads, wl.n_kv_heads, wl.head_dim
     kt, vt = _rand_bits(rng, (3, hkv, d)), _rand_bits(rng, (3, hkv, d))
@@ -296,37 +320,67 @@ def test_select_ties_and_override():
     cache.close()
 
 
-@pytest.mark.parametrize("name,merge,layers", [
-    ("tiny", False, [0]), ("tiny", True, [0]),
-    ("single_image", True, [0, 3]),
-    ("tiled_image", True, [0, 7]), ("tiled_image", False, [1]),
-])
-def test_lockstep_small_workloads(name, merge, layers):
+def _layer_cases():
+    """Every layer of every workload, merge on; plus the paper's own method (merge off) on a few."""
+    cases = []
+    for name in ("tiny", "single_image", "tiled_image", "video", "long_video"):
+        wl = get_workload(name)
+        cases += [(name, True, layer) for layer in range(wl.n_layers)]
+    cases += [("tiny", False, 0), ("single_image", False, 2), ("tiled_image", False, 1), ("video", False, 9),
+              ("long_video", False, 17)]
+    return cases
+
+
+@pytest.mark.parametrize("name,merge,layer", _layer_cases())
+def test_lockstep_every_layer(name, merge, layer):
+    """All five workloads, every layer, in lock-step with the oracle in the launch configuration the
+    benchmark times (all layers in one cache, two scratch sets): attention outputs within 2e-2, the
+    library's own scores within 1e-3 relative on every evicting block, and under the oracle's
+    scores kept sets, merge plans, token indices and weights bit-exact, rows within one bf16 ulp."""
     wl = get_workload(name)
     cache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
-                    wl.segments, merge=merge, device=DEV)
-    for layer in layers:
-        qb, kb, vb = layer_inputs(wl, layer)
-        stats = {}
-        U.lockstep_layer(wl, layer, cache, qb, kb, vb, merge, stats=stats)
-        print(name, "layer", layer, "merge", merge, stats, flush=True)
-        if merge:
-            assert stats["merged"] > 0
+                    wl.segments, merge=merge, scratch_sets=min(2, wl.n_layers), device=DEV)
+    qb, kb, vb = layer_inputs(wl, layer)
+    stats = {}
+    U.lockstep_layer(wl, layer, cache, qb, kb, vb, merge, stats=stats)
+    print(name, "layer", layer, "merge", merge, stats, flush=True)
+    assert stats["scored_blocks"] == sum(1 for t0, n in chunk_ranges(wl.n_tokens, wl.chunk) if t0 + n > wl.budget)
+    assert stats["score_rel"] <= U.SCORE_RTOL
+    if merge:
+        assert stats["merged"] > 0
     cache.close()
 
 
-@pytest.mark.parametrize("name,layer", [("video", 0), ("video", 15), ("long_video", 0), ("long_video", 31)])
-def test_lockstep_full_size_sampled_layers(name, layer):
-    """Full-size shapes in the launch configuration the benchmark times; the
-    oracle is affordable for single layers."""
+@pytest.mark.parametrize("name", ["tiny", "single_image", "tiled_image"])
+def test_free_running_overlap_with_the_oracle(name):
+    """Free-running report: the library runs the whole prefill on its OWN scores, the oracle on its
+    own; nothing is re-synchronised.  Scores agree to about 1e-5, so the two only part where two
+    candidates are nearly tied, and a different choice then changes the cache both go on with.
+    Reported per KV head: Jaccard overlap of the final kept token sets; and the error of the last
+    block's attention output, which has seen every difference before it."""
     wl = get_workload(name)
     cache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
-                    wl.segments, merge=True, scratch_sets=2, device=DEV)
-    qb, kb, vb = layer_inputs(wl, layer)
-    stats = {}
-    U.lockstep_layer(wl, layer, cache, qb, kb, vb, True, stats=stats)
-    print(name, "layer", layer, stats, flush=True)
-    assert stats["merged"] > 0
+                    wl.segments, merge=True, scratch_sets=min(2, wl.n_layers), device=DEV)
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    overlaps, out_errs = [], []
+    for layer in range(wl.n_layers):
+        qb, kb, vb = layer_inputs(wl, layer)
+        qt, kt, vt = (U.bits_to_torch(x) for x in (qb, kb, vb))
+        q64, k64, v64 = (bf16_bits_to_f32(x).astype(np.float64) for x in (qb, kb, vb))
+        out = None
+        for t0, n in ranges:
+            out = cache.prefill_chunk(layer, t0, qt[t0:t0 + n], kt[t0:t0 + n], vt[t0:t0 + n])
+            cache.compact(layer)
+        oc, recs = O.prefill_layer(q64, k64, v64, wl.chunk, wl.budget, wl.segments, True)
+        k, v, idx, w, count, nxt = cache.decode_ready(layer)
+        assert count == oc.count and nxt == wl.n_tokens
+        idx = idx.cpu().numpy()
+        overlaps += [U.jaccard(idx[hk, :count], oc.idx[hk]) for hk in range(wl.n_kv_heads)]
+        out_errs.append(U.out_rel_err(U.torch_bf16_to_f64(out), recs[-1]["out"]))
+    print("free-running %s: kept-set Jaccard per head min %.4f mean %.4f; last-block out rel err max %.4g"
+          % (name, min(overlaps), float(np.mean(overlaps)), max(out_errs)), flush=True)
+    assert min(overlaps) >= FREE_RUNNING_JACCARD_FLOOR
+    assert max(out_errs) <= FREE_RUNNING_OUT_TOL
     cache.close()
 
 
@@ -504,5 +558,129 @@ def test_compaction_on_a_second_stream_changes_nothing(name, sets, scoring):
     for a, b in zip(*results):
         assert a[4] == b[4] and a[5] == b[5]
         for x, y in zip(a[:4] + (a[6],), b[:4] + (b[6],)):
+            assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                               y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
+
+
+def test_real_cache_refuses_null_tensors():
+    """A cache on a live allocation (not a dry run) returns KVP_EINVAL for a null tensor before it
+    enqueues anything, and stays usable."""
+    wl = get_workload("tiny")
+    cache = K.Cache(1, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments, device=DEV)
+    qb, kb, vb = layer_inputs(wl, 0)
+    qt, kt, vt = (U.bits_to_torch(x)[:8].contiguous() for x in (qb, kb, vb))
+    out = torch.empty_like(qt)
+    ptrs = [qt.data_ptr(), kt.data_ptr(), vt.data_ptr(), out.data_ptr()]
+    for hole in range(4):
+        args = list(ptrs)
+        args[hole] = 0
+        assert K.kvp_prefill_chunk(cache.handle, 0, 0, 8, *args) == K.KVP_EINVAL
+    assert K.kvp_decode_step(cache.handle, 0, 0, kt.data_ptr(), vt.data_ptr(), 1, out.data_ptr()) == K.KVP_EINVAL
+    rc, vw = K.kvp_decode_ready(cache.handle, 0)
+    assert rc == K.KVP_OK and (vw.count, vw.next_token) == (0, 0)          # nothing moved
+    assert K.kvp_prefill_chunk(cache.handle, 0, 0, 8, *ptrs) == K.KVP_OK
+    assert K.kvp_compact(cache.handle, 0) == K.KVP_OK
+    torch.cuda.synchronize()
+    cache.close()
+
+
+@pytest.mark.parametrize("name,stop_after", [("tiny", 4), ("tiled_image", 5)])
+def test_snapshot_restore_continue_is_bit_identical(name, stop_after):
+    """Checkpoint and resume: the cache is the resumable state.  Run some blocks, copy out
+    (K, V, token index, weight, count, next token) of every layer, free the cache, create a new one
+    on a new buffer, write the copies back through the kvp_decode_ready pointers, declare them with
+    kvp_set_state and go on: every later output and the final caches must equal, bit for bit,
+    those of the run that was never interrupted."""
+    wl = get_workload(name)
+    layers = min(wl.n_layers, 3)
+    data = [tuple(U.bits_to_torch(x) for x in layer_inputs(wl, l)) for l in range(layers)]
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+
+    def make():
+        return K.Cache(layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments,
+                       merge=True, device=DEV)
+
+    def run(cache, blocks):
+        outs = []
+        for t0, n in blocks:
+            for l in range(layers):
+                q, k, v = (x[t0:t0 + n] for x in data[l])
+                outs.append(cache.prefill_chunk(l, t0, q, k, v).clone())
+                cache.compact(l)
+        return outs
+
+    def state(cache):
+        st = []
+        for l in range(layers):
+            k, v, idx, w, count, nxt = cache.decode_ready(l)
+            st.append((k[:, :count].clone(), v[:, :count].clone(), idx[:, :count].clone(), w[:, :count].clone(), count, nxt))
+        return st
+
+    straight = make()
+    outs_a = run(straight, ranges)
+    final_a = state(straight)
+    straight.close()
+
+    first = make()
+    run(first, ranges[:stop_after])
+    snap = state(first)
+    torch.cuda.synchronize()
+    first.close()
+    del first
+    second = make()
+    for l, (k, v, idx, w, count, nxt) in enumerate(snap):
+        k2, v2, idx2, w2, _, _ = second.decode_ready(l)
+        k2[:, :count] = k
+        v2[:, :count] = v
+        idx2[:, :count] = idx
+        w2[:, :count] = w
+        second.set_state(l, count, nxt)
+    outs_b = run(second, ranges[stop_after:])
+    final_b = state(second)
+    second.close()
+
+    bits = lambda t: t.view(torch.int16) if t.dtype == torch.bfloat16 else t
+    tail = outs_a[stop_after * layers:]
+    assert len(tail) == len(outs_b)
+    for a, b in zip(tail, outs_b):
+        assert torch.equal(bits(a), bits(b))
+    for a, b in zip(final_a, final_b):
+        assert a[4] == b[4] and a[5] == b[5]
+        for x, y in zip(a[:4], b[:4]):
+            assert torch.equal(bits(x), bits(y))
+
+
+def test_second_stream_with_freshly_allocated_blocks():
+    """With compactions on the side stream a block's K and V are read after Prefill.block has
+    returned.  A caller that allocates them per block and drops them at once must still get the
+    in-order result: the driver keeps them alive (and out of the allocator's hands) until the
+    side stream is done with them."""
+    wl = get_workload("tiled_image")
+    layers = 4
+    host = [layer_inputs(wl, l) for l in range(layers)]
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    results = []
+    for overlap in (False, True):
+        cache = K.Cache(layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments,
+                        merge=True, scratch_sets=4 if overlap else 1, device=DEV)
+        driver = K.Prefill(cache, layers, overlap=overlap)
+        for t0, n in ranges:
+            def fresh(l):
+                return tuple(U.bits_to_torch(x[t0:t0 + n]) for x in host[l])     # new device tensors, dropped after the call
+            driver.block(t0, fresh)
+            # churn the caching allocator: tensors of the sizes just dropped, overwritten at once
+            junk = [torch.full((n, wl.n_kv_heads, wl.head_dim), float("nan"), dtype=torch.bfloat16, device=DEV)
+                    for _ in range(2 * layers)]
+            del junk
+        driver.finish()
+        torch.cuda.synchronize()
+        st = []
+        for l in range(layers):
+            k, v, idx, w, count, nxt = cache.decode_ready(l)
+            st.append((k[:, :count].clone(), v[:, :count].clone(), idx[:, :count].clone(), w[:, :count].clone()))
+        results.append(st)
+        cache.close()
+    for a, b in zip(*results):
+        for x, y in zip(a, b):
             assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
                                y.view(torch.int16) if y.dtype == torch.bfloat16 else y)

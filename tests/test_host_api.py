@@ -242,11 +242,7 @@ def test_null_handles():
     rc, _ = K.kvp_decode_ready(None, 0)
     assert rc == K.KVP_EINVAL
     K.kvp_free_cache(None)
-    wl = get_workload("tiny")
-    rc, h = K.kvp_init_cache(_cfg(wl, flags=0), wl.segments, 4096, 1 << 30)
-    # a real (non dry-run) cache refuses null tensors before launching anything
-    if rc == K.KVP_OK:
-        assert K.kvp_prefill_chunk(h, 0, 0, 8, 0, 0, 0, 0) == K.KVP_EINVAL
-        K.kvp_free_cache(h)
-    else:
-        assert rc == K.KVP_EDEVICE      # no GPU here: the init kernel could not be enqueued
+    # Every cache this file creates is a dry run or is refused by validation: no call here may
+    # reach a kernel launch, so no device pointer is ever made up for a cache that would use it.
+    # "A real cache refuses null tensors before launching anything" is checked on a live
+    # allocation in tests/test_gpu_parity.py::test_real_cache_refuses_null_tensors.

@@ -50,6 +50,36 @@ def test_bf16_bits_roundtrip():
     assert np.array_equal(O.f64_to_bf16_bits(O.bf16_bits_to_f64(bits)), bits)
 
 
+def test_bf16_bit_helpers_against_the_format_and_a_library_view():
+    """Every finite bfloat16 pattern (both signs, zeros, subnormals, the largest finite value):
+    the value must be what torch reads out of the same 16 bits, and what the format's definition
+    gives, (-1)^s 2^(e-127) (1 + m/128), or (-1)^s 2^-126 (m/128) for e = 0; and the way back must
+    return the same 16 bits."""
+    bits = np.arange(1 << 16, dtype=np.uint32)
+    e, m, sgn = (bits >> 7) & 0xFF, bits & 0x7F, np.where(bits >> 15, -1.0, 1.0)
+    finite = e != 0xFF
+    bits, e, m, sgn = bits[finite].astype(np.uint16), e[finite], m[finite], sgn[finite]
+    assert len(bits) == 65536 - 256
+    got = O.bf16_bits_to_f64(bits)
+    by_library = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, by_library) and np.array_equal(np.signbit(got), np.signbit(by_library))
+    by_definition = sgn * np.where(e == 0, np.ldexp(m / 128.0, -126), np.ldexp(1.0 + m / 128.0, e.astype(np.int64) - 127))
+    assert np.array_equal(got, by_definition)
+    # spot values nobody computes: 0x3F80 is 1, 0xC000 is -2, 0x3DCD is the bf16 next to 0.1, 0x7F7F the largest
+    assert O.bf16_bits_to_f64(np.array([0x3F80, 0xC000, 0x0000, 0x7F7F], dtype=np.uint16)).tolist() == \
+        [1.0, -2.0, 0.0, (2.0 - 2.0 ** -7) * 2.0 ** 127]
+    assert abs(O.bf16_bits_to_f64(np.array([0x3DCD], dtype=np.uint16))[0] - 0.1) < 0.1 * 2.0 ** -8
+    # the way back: the same bits, the sign of zero included
+    back = O.f64_to_bf16_bits(by_library)
+    assert back.dtype == np.uint16 and np.array_equal(back, bits)
+    by_library_back = torch.from_numpy(by_library).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(back, by_library_back)
+    # values that are not bfloat16 numbers are refused, not rounded
+    for bad in (1.0 + 2.0 ** -8, 0.1, 1e-50, 1e39):
+        with pytest.raises(ValueError):
+            O.f64_to_bf16_bits(np.array([bad]))
+
+
 # ---------------------------------------------------------------- Eq. 2
 def test_kv_bytes_closed_form():
     # Eq. 2 at the budget, bf16: the persistent KV sizes of the five shapes
