@@ -220,6 +220,29 @@ int kvp_decode_ready(kvp_cache* cache, int32_t layer, kvp_view* out);
 int kvp_decode_step(kvp_cache* cache, int32_t layer, const void* q, const void* k_tail, const void* v_tail,
                     int32_t n_tail, void* out, void* stream);
 
+/* kvp_decode_step for callers that cannot allocate and cannot lend scratch memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same result (bit for bit when the same number of
+ * workgroups per KV head is used, which is the case whenever both calls succeed
+ * at the sizes below), but the partial results of the step go to a file-scope
+ * device array of KVP_STATIC_SCRATCH_BYTES that the library holds on every GPU
+ * it is used on (its address is looked up once per GPU, at kvp_init_cache),
+ * not to the layer's scratch set.  The call allocates nothing, synchronises
+ * nothing, and does not care whether the scratch set is taken by a pending block
+ * (the layer itself must be READY).
+ *   KVP_ENOMEM  the step's partial results do not fit: with s = min(128,
+ *               ceil((count + n_tail) / 64)) workgroups per KV head wanted, at
+ *               least min(s, KVP_STATIC_MIN_SPLITS) sets of n_q_heads *
+ *               (head_dim + 2) floats must fit into the array.
+ *   KVP_EDEVICE the array's address could not be looked up on this GPU.
+ * All calls on one GPU share that GPU's array and every call overwrites what the
+ * last one left (nothing in it needs clearing): calls that may overlap on one
+ * GPU, on different streams or from different caches, race and must be ordered
+ * by the caller.  Other errors as for kvp_decode_step. */
+enum { KVP_STATIC_SCRATCH_BYTES = 1 << 20, KVP_STATIC_MIN_SPLITS = 16 };
+int kvp_decode_step_static(kvp_cache* cache, int32_t layer, const void* q, const void* k_tail,
+                           const void* v_tail, int32_t n_tail, void* out, void* stream);
+
 /* Resume: declare that the caller has written `count` valid slots per head
  * into the layer's K, V, token_idx and weight (through the kvp_view pointers)
  * and that the next block starts at `next_token`.  Layer becomes READY. */

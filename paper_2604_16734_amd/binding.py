@@ -95,6 +95,8 @@ def lib():
         L.kvp_compact.argtypes = [vp, i32, vp, vp]
         L.kvp_decode_step.restype = ctypes.c_int
         L.kvp_decode_step.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp]
+        L.kvp_decode_step_static.restype = ctypes.c_int
+        L.kvp_decode_step_static.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp]
         L.kvp_decode_ready.restype = ctypes.c_int
         L.kvp_decode_ready.argtypes = [vp, i32, P(KvpView)]
         L.kvp_set_state.restype = ctypes.c_int
@@ -165,7 +167,12 @@ def kvp_decode_step(handle, layer, q, k_tail, v_tail, n_tail, out, stream=0):
     return lib().kvp_decode_step(handle, layer, q, k_tail, v_tail, n_tail, out, stream)
 
 
+def kvp_decode_step_static(handle, layer, q, k_tail, v_tail, n_tail, out, stream=0):
+    return lib().kvp_decode_step_static(handle, layer, q, k_tail, v_tail, n_tail, out, stream)
+
+
 KVP_SCORE_OWN, KVP_SCORE_PROXY, KVP_SCORE_KEYDIFF = 0, 1, 2
+KVP_STATIC_SCRATCH_BYTES, KVP_STATIC_MIN_SPLITS = 1 << 20, 16
 
 
 def _ptr_array(ptrs):
@@ -328,6 +335,17 @@ class Cache:
         rc = kvp_decode_step(self.handle, layer, self._ptr(q, bf), self._ptr(k_tail, bf), self._ptr(v_tail, bf),
                              n_tail, self._ptr(out, bf), self._stream(stream))
         _check(rc, "kvp_decode_step")
+        return out
+
+    def decode_step_static(self, layer, q, k_tail, v_tail, out, stream=None):
+        """decode_step with the library's static scratch; `out` must be given (nothing is allocated)."""
+        bf = self.torch.bfloat16
+        assert q.shape == out.shape == (self.cfg.n_q_heads, self.cfg.head_dim)
+        n_tail = k_tail.shape[0]
+        assert k_tail.shape == v_tail.shape == (n_tail, self.cfg.n_kv_heads, self.cfg.head_dim)
+        rc = kvp_decode_step_static(self.handle, layer, self._ptr(q, bf), self._ptr(k_tail, bf), self._ptr(v_tail, bf),
+                                    n_tail, self._ptr(out, bf), self._stream(stream))
+        _check(rc, "kvp_decode_step_static")
         return out
 
     def prefill_chunk_proxy(self, layer, token_begin, q, k, v, q_obs, out=None, stream=None):

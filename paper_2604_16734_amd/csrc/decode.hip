@@ -19,7 +19,13 @@
 // LDS across waves) and leaves (max, sum, unnormalised output) per query head; a
 // second small kernel folds the workgroups' partials in a fixed order and rounds
 // once to bfloat16.
+#include <mutex>
+
 #include "kvp_internal.h"
+
+// Scratch of kvp_decode_step_static (the entry point for callers that cannot allocate): the
+// partial results of the step, KVP_STATIC_SCRATCH_BYTES per GPU, held until the process ends.
+static __device__ __align__(256) float scratch[KVP_STATIC_SCRATCH_BYTES / sizeof(float)];
 
 namespace kvp {
 namespace {
@@ -235,9 +241,44 @@ hipError_t launch_for(const DecodeArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---- kvp_decode_step_static: the partial results live in a file-scope device array instead of
+// the cache's scratch set.  Every GPU the library runs on holds its own copy of the array, at its
+// own address, until the process ends; host code never uses the array's name as an address, only
+// the pointer hipGetSymbolAddress gave for the device in question.
+constexpr size_t kStaticScratchFloats = sizeof(scratch) / sizeof(float);
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
 }  // namespace
 
+// Looks the array's address up for the CURRENT device (once per device) and returns it.
+hipError_t decode_static_scratch(float** ptr, size_t* n_floats) {
+  *ptr = nullptr;
+  *n_floats = kStaticScratchFloats;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 int decode_max_group() { return kGroupLimit; }
+
+// workgroups per KV head the step would like: one per 64-key tile, kMaxSplits at most
+int decode_splits_wanted(long long n_keys) {
+  const long long want = (n_keys + kTile - 1) / kTile;
+  return (int)(want > kMaxSplits ? kMaxSplits : want);
+}
 
 // workgroups per KV head: one per 64-key tile while the partials fit, kMaxSplits at most
 // (every workgroup then has at least one tile)

@@ -115,6 +115,8 @@ struct kvp_cache {
   float scale;
   bool dry;
   int attn_shape = -1;                // kvp_set_attention_shape; < 0: chosen per launch
+  float* static_scratch = nullptr;    // the file-scope scratch array on this cache's device
+  size_t static_scratch_floats = 0;
   bool profiling = false;
   std::vector<ProfEvent> events;      // recorded, not yet read
   std::vector<hipEvent_t> pool;       // idle events
@@ -312,6 +314,7 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
     const size_t slots = (size_t)cfg->n_layers * lay.meta_layer_elems;
     hipError_t e = prepare_attention();
     if (e == hipSuccess) e = prepare_select();
+    if (e == hipSuccess) e = decode_static_scratch(&c->static_scratch, &c->static_scratch_floats);
     if (e == hipSuccess)
       e = launch_init(c->idx(0), c->weight(0), slots, c->segs.data(), n_segs, c->dev_segs(),
                       static_cast<hipStream_t>(stream));
@@ -584,6 +587,39 @@ int kvp_decode_step(kvp_cache* c, int32_t layer, const void* q, const void* k_ta
   const size_t have = (size_t)cfg.n_kv_heads * lay.max_partials * lay.cand_stride;   // floats
   da.n_splits = decode_splits((long long)L.count + n_tail, cfg.head_dim, have, cfg.n_q_heads);
   if (da.n_splits < 1) return KVP_ENOMEM;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  return launch(c, KVP_K_DECODE, s, [&] { return launch_decode(da, cfg.head_dim, s); });
+}
+
+int kvp_decode_step_static(kvp_cache* c, int32_t layer, const void* q, const void* k_tail, const void* v_tail,
+                           int32_t n_tail, void* out, void* stream) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  if (n_tail < 1 || n_tail > (1 << 20)) return KVP_EINVAL;
+  if (!c->dry && (!q || !k_tail || !v_tail || !out)) return KVP_EINVAL;
+  const kvp_config& cfg = c->cfg;
+  if (cfg.n_q_heads / cfg.n_kv_heads > decode_max_group()) return KVP_EINVAL;
+  const Layer& L = c->layers[layer];
+  if (L.state != READY) return KVP_ESTATE;
+  // the partial results must fit the static array with enough workgroups per KV head to be worth
+  // running: all the step wants, or KVP_STATIC_MIN_SPLITS of them
+  const size_t have = KVP_STATIC_SCRATCH_BYTES / sizeof(float);
+  const int want = decode_splits_wanted((long long)L.count + n_tail);
+  const int splits = decode_splits((long long)L.count + n_tail, cfg.head_dim, have, cfg.n_q_heads);
+  if (splits < (want < KVP_STATIC_MIN_SPLITS ? want : KVP_STATIC_MIN_SPLITS)) return KVP_ENOMEM;
+  if (c->dry) return KVP_OK;
+  if (!c->static_scratch || c->static_scratch_floats < have) return KVP_EDEVICE;
+  DecodeArgs da{};
+  da.q = static_cast<const u16*>(q);
+  da.k_tail = static_cast<const u16*>(k_tail);
+  da.v_tail = static_cast<const u16*>(v_tail);
+  da.out = static_cast<u16*>(out);
+  da.k_cache = c->k_cache(layer);
+  da.v_cache = c->v_cache(layer);
+  da.partial = c->static_scratch;       // the looked-up device address, never the array's name
+  da.c = L.count; da.n_tail = n_tail;
+  da.n_q_heads = cfg.n_q_heads; da.n_kv_heads = cfg.n_kv_heads; da.budget = cfg.budget;
+  da.scale_log2 = c->scale * 1.4426950408889634f;
+  da.n_splits = splits;
   hipStream_t s = static_cast<hipStream_t>(stream);
   return launch(c, KVP_K_DECODE, s, [&] { return launch_decode(da, cfg.head_dim, s); });
 }

@@ -93,7 +93,10 @@ struct DecodeArgs {
 };
 int decode_max_group();
 int decode_splits(long long n_keys, int head_dim, size_t scratch_floats, int n_q_heads);
+int decode_splits_wanted(long long n_keys);
 hipError_t launch_decode(const DecodeArgs& a, int head_dim, hipStream_t s);
+// address and size of the file-scope scratch array on the current device (kvp_decode_step_static)
+hipError_t decode_static_scratch(float** ptr, size_t* n_floats);
 
 // Device copy of one prefix segment.
 struct Seg {

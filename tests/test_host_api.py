@@ -179,6 +179,32 @@ def test_decode_step_state_machine():
         K.kvp_free_cache(h)
 
 
+def test_static_scratch_decode_step_limits():
+    """kvp_decode_step_static refuses a step whose partial results do not fit its 1 MiB array with
+    at least 16 workgroups per KV head (or all it wants, if fewer), and follows the state machine
+    of kvp_decode_step except that a taken scratch set does not matter."""
+    from kvp_workload import Segment, Workload
+    segs = (Segment(0, 4096, 0),)
+    fits = Workload("fits", 2, 64, 8, 128, 64, 1024, segs)          # 64 heads x 130 floats x 16 = 133120 floats
+    too_big = Workload("too_big", 2, 128, 8, 128, 64, 1024, segs)   # 128 heads: only 15 sets of partials fit
+    for wl, many_keys_rc in ((fits, K.KVP_OK), (too_big, K.KVP_ENOMEM)):
+        rc, h = K.kvp_init_cache(_cfg(wl), wl.segments, None, 0)
+        assert rc == K.KVP_OK
+        try:
+            assert K.kvp_decode_step_static(h, 0, 0, 0, 0, 1, 0) == K.KVP_OK           # one key: one workgroup is all it wants
+            assert K.kvp_decode_step_static(h, 0, 0, 0, 0, 0, 0) == K.KVP_EINVAL
+            assert K.kvp_decode_step_static(h, 9, 0, 0, 0, 1, 0) == K.KVP_EINVAL
+            assert K.kvp_set_state(h, 0, 1024, 1024) == K.KVP_OK
+            assert K.kvp_decode_step_static(h, 0, 0, 0, 0, 1, 0) == many_keys_rc       # 17 workgroups wanted
+            assert K.kvp_decode_step(h, 0, 0, 0, 0, 1, 0) == K.KVP_OK                  # the scratch set is roomier
+            assert K.kvp_prefill_chunk(h, 1, 0, 16, 0, 0, 0, 0) == K.KVP_OK            # layer 1 pending, set taken
+            assert K.kvp_decode_step_static(h, 1, 0, 0, 0, 1, 0) == K.KVP_ESTATE
+            assert K.kvp_decode_step(h, 0, 0, 0, 0, 1, 0) == K.KVP_ESTATE
+            assert K.kvp_decode_step_static(h, 0, 0, 0, 0, 1, 0) == many_keys_rc
+        finally:
+            K.kvp_free_cache(h)
+
+
 def test_prefill_block_walks_every_layer():
     """kvp_prefill_block in a dry run (no device work, so everything on one stream): every layer
     advances by the block, errors are reported before any layer moves, and a per-layer call that
