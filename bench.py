@@ -8,12 +8,18 @@ resident in HBM.  The metric is prefill tokens/s at the fixed KV budget.
 
 Prints ONE JSON line.  `roofline` is for the attention kernel (the dominant
 one): algorithmic flops 4 d Hq (n c + n (n + 1) / 2) per launch over its HIP
-event time on the launching stream.  `cpu_baseline` is the NumPy oracle timed
-on this machine's host cores on a bounded sample of the same workload.
+event time on the launching stream.  `rooflines` has an entry for every kernel
+of the path (scoring against its own MFMA flops; select, merge, move and the
+decode step against HBM, with the bytes taken from what this run's compactions
+actually did).  `attainable` holds what this GPU reaches on a register-resident
+bf16 MFMA loop and on a plain device copy, measured in the same run, and every
+roofline entry also gives its fraction of those.  `cpu_baseline` is the NumPy
+oracle timed on this machine's host cores on a bounded sample of the same workload.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -58,18 +64,77 @@ def generate(wl, device, threads):
     return out
 
 
-def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None, keydiff=False):
+def run_steps(driver, cache, wl, data, ranges, steps, outs, obs=None, keydiff=False, events=None):
     """`steps` whole prefills: every block through every layer, in the order `driver` gives
     (compactions in line, or on a second stream beside the following layers' attention).
     `obs`: per-layer proxy queries that score the candidates instead of the block's own;
-    `keydiff`: the keys alone score them."""
+    `keydiff`: the keys alone score them.  `events`: a list that receives one (start, end) pair
+    of HIP events per step, recorded on the main stream (the end after the side stream has been
+    joined), for the per-step median."""
+    import torch
     for _ in range(steps):
+        if events is not None:
+            start = torch.cuda.Event(enable_timing=True)
+            start.record()
         for layer in range(wl.n_layers):
             cache.set_state(layer, 0, 0)
         for t0, n in ranges:
             driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n],
                          (lambda l: obs[l]) if obs is not None else None, keydiff)
+        if events is not None:
+            driver.finish()
+            end = torch.cuda.Event(enable_timing=True)
+            end.record()
+            events.append((start, end))
     driver.finish()
+
+
+def attainable_peaks(device):
+    """What this GPU reaches on (a) dense 32x32x16 bf16 MFMAs on register operands, eight waves on
+    every CU, no memory traffic, and (b) a plain 256 MiB device copy (bytes read + bytes written).
+    Medians of five launches each, timed with HIP events on the launching stream."""
+    import torch
+    import paper_2604_16734_amd as K
+    stream = torch.cuda.current_stream(device).cuda_stream
+    cus = torch.cuda.get_device_properties(device).multi_processor_count
+    sink = torch.empty(cus * 512, dtype=torch.float32, device=device)
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        out = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            b.synchronize()
+            out.append(a.elapsed_time(b) * 1e-3)
+        return statistics.median(out)
+
+    flops = [0.0]
+
+    def mfma():
+        rc, flops[0] = K.kvp_probe_mfma(sink.data_ptr(), sink.numel() * 4, cus, 12000, stream)
+        if rc:
+            raise K.KvpError(rc, "kvp_probe_mfma")
+    t_mfma = timed(mfma)
+    nbytes = 256 << 20
+    src = torch.empty(nbytes, dtype=torch.uint8, device=device).fill_(3)
+    dst = torch.empty_like(src)
+    best = 0.0
+    for wgs in (cus * 4, cus * 8, cus * 16, cus * 32):
+        def copy():
+            rc = K.kvp_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, wgs, stream)
+            if rc:
+                raise K.KvpError(rc, "kvp_probe_copy")
+        best = max(best, 2 * nbytes / timed(copy))
+    assert bool((dst == 3).all())
+    del src, dst
+    return {"mfma_bf16_tflops": round(flops[0] / t_mfma / 1e12, 1), "hbm_copy_GBps": round(best / 1e9, 1),
+            "compute_units": cus,
+            "how": "kvp_probe_mfma: %d workgroups x 8 waves x 192000 MFMAs 32x32x16 bf16 on registers; "
+                   "kvp_probe_copy: 256 MiB, read + written bytes, best of four grid sizes; medians of 5" % cus}
 
 
 def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=8, variants=True):
@@ -88,11 +153,13 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
             for _ in range(wl.n_layers)]
     run_steps(driver, cache, wl, data, ranges, warmup, outs)
     torch.cuda.synchronize()
+    step_events = []
     t_begin = time.perf_counter()
-    run_steps(driver, cache, wl, data, ranges, steps, outs)
+    run_steps(driver, cache, wl, data, ranges, steps, outs, events=step_events)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
     ms_per_step = 1e3 * elapsed / steps
+    ms_median = statistics.median(a.elapsed_time(b) for a, b in step_events)
     proxy = None
     if n_obs and variants:
         # the paper's literal scoring (Sec. 3.2): n_obs proxy queries per layer, the same for every block
@@ -162,7 +229,7 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         cache.profile_enable(True)
         decode_tokens(2)
         torch.cuda.synchronize()
-        dec_launches, dec_ms = cache.profile_read()["decode"]
+        dec_launches, dec_ms, _ = cache.profile_read()["decode"]
         cache.profile_enable(False)
         kept = min(wl.budget, wl.n_tokens)
         dec_bytes = 2 * wl.n_kv_heads * (kept + 1) * wl.head_dim * 2      # K and V rows of one layer, read once
@@ -176,6 +243,7 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         "proxy_scoring": proxy,
         "tokens_per_s": wl.n_tokens / (elapsed / steps),
         "ms_per_step": ms_per_step,
+        "ms_per_step_median_hip_events": ms_median,
         "persistent_kv_bytes": cache.persistent_bytes,
         "scratch_bytes": cache.nbytes - cache.persistent_bytes,
         "chunk_kv_bytes": 2 * wl.chunk * wl.n_kv_heads * wl.head_dim * 2,
@@ -183,6 +251,7 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
     }
     if profile:
         prof_steps = 1
+        totals_before = cache.totals()
         cache.profile_enable(True)
         torch.cuda.synchronize()
         t_begin = time.perf_counter()
@@ -196,24 +265,43 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         flops_layer, _ = attention_flops(wl, ranges)
         flops_step = flops_layer * wl.n_layers
         kern = {}
-        for name, (launches, ms) in stats.items():
+        for name, (launches, ms, layers) in stats.items():
             if launches:
-                kern[name] = {"launches_per_step": launches // prof_steps, "ms_per_step": ms / prof_steps,
-                              "avg_us": 1e3 * ms / launches}
+                kern[name] = {"launches_per_step": launches // prof_steps, "layers_per_launch": layers / launches,
+                              "ms_per_step": ms / prof_steps, "avg_us": 1e3 * ms / launches}
         res["kernels"] = kern
         att_ms = stats["attention"][1] / prof_steps
-        col_ms = stats["colsum"][1] / prof_steps
+        col_ms = stats["colsum"][1] / prof_steps      # 0 when the scores come out of the attention launch itself
         res["attention_tflops"] = flops_step / (att_ms * 1e-3) / 1e12
         res["attention_plus_scoring_tflops"] = flops_step / ((att_ms + col_ms) * 1e-3) / 1e12
         res["attention_flops_per_launch"] = flops_step / stats["attention"][0] * prof_steps
-        # bytes the compaction kernels must move: per kept block row 2 x (read + write) of d bf16
-        row = wl.head_dim * 2
-        moved = 0
+        # ---- what the compactions of that pass actually did, and the bytes that takes
+        done = {k: v - totals_before[k] for k, v in cache.totals().items()}
+        row = wl.head_dim * 2                       # bytes of one K or V row
+        appended, select_bytes, colsum_flops, evicting_launches = 0, 0, 0, 0
         c = 0
         for _, n in ranges:
-            moved += 2 * 2 * row * n * wl.n_kv_heads        # every block row is written once at most
+            if c + n <= wl.budget:
+                appended += n * wl.n_kv_heads
+            else:
+                # score and token index of every candidate in, keep flag and merge target out
+                select_bytes += (c + n) * wl.n_kv_heads * (4 + 4 + 1 + 4)
+                colsum_flops += 2 * wl.head_dim * wl.n_q_heads * (n * c + n * (n + 1) // 2)
+                evicting_launches += 1
             c = min(wl.budget, c + n)
-        res["move_bytes_bound_per_step"] = moved * wl.n_layers
+        appended *= wl.n_layers * prof_steps
+        select_bytes = select_bytes * wl.n_layers * prof_steps + done["moved_rows"] * 16 + done["merge_destinations"] * 32
+        colsum_flops *= wl.n_layers * prof_steps
+        # a moved row: K and V read and written, token index and weight written, its plan entry read
+        move_bytes = (appended + done["moved_rows"]) * (4 * row + 8) + done["moved_rows"] * 16
+        # a merge: destination and sources read (K, V and weight), destination written, its plan entry read
+        merge_bytes = ((done["merge_destinations"] + done["merge_sources"]) * (2 * row + 4)
+                       + done["merge_destinations"] * (2 * row + 4 + 32))
+        res["compaction_totals_per_step"] = {k: v // prof_steps for k, v in done.items()}
+        res["compaction_totals_per_step"]["appended_rows"] = appended // prof_steps
+        res["hbm_bytes_per_step"] = {"select": select_bytes // prof_steps, "merge": merge_bytes // prof_steps,
+                                     "move": move_bytes // prof_steps}
+        res["colsum_flops_per_step"] = colsum_flops // prof_steps
     cache.close()
     del data
     torch.cuda.empty_cache()
@@ -278,6 +366,8 @@ def main():
                     help="also time the prefill scored with this many proxy queries (0: skip)")
     ap.add_argument("--variants", type=int, default=1,
                     help="also time proxy-query and key-only scoring, the bulk first pass and the decode step")
+    ap.add_argument("--peaks", type=int, default=1,
+                    help="also measure what this GPU attains on a register-resident bf16 MFMA loop and a device copy")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -317,8 +407,46 @@ def main():
                     "persistent_kv_bytes": r["persistent_kv_bytes"],
                 }
 
+    peaks = attainable_peaks(device) if args.peaks else None
     att = main_res["kernels"]["attention"]
     achieved = main_res["attention_tflops"]
+    kern = main_res["kernels"]
+
+    def entry(kernel, bound, achieved_v, unit, per_launch_key, per_launch, note=None):
+        peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_HBM_GBS
+        e = {"kernel": kernel, "bound": bound, "achieved": round(achieved_v, 2), "peak": peak, "unit": unit,
+             "frac": round(achieved_v / peak, 4), "avg_launch_us": round(kern[kernel]["avg_us"], 2),
+             per_launch_key: per_launch}
+        if peaks:
+            got = peaks["mfma_bf16_tflops"] if bound == "mfma" else peaks["hbm_copy_GBps"]
+            e["frac_of_attainable"] = round(achieved_v / got, 4)
+        if note:
+            e["note"] = note
+        return e
+
+    rooflines = [entry("attention", "mfma", achieved, "TFLOP/s", "flops_per_launch", main_res["attention_flops_per_launch"])]
+    if "colsum" in kern:
+        f = main_res["colsum_flops_per_step"]
+        rooflines.append(entry("colsum", "mfma", f / (kern["colsum"]["ms_per_step"] * 1e-3) / 1e12, "TFLOP/s",
+                               "flops_per_launch", f / kern["colsum"]["launches_per_step"],
+                               "the second QK^T sweep's own flops 2 d Hq (n c + n (n + 1) / 2); they are not "
+                               "counted as algorithmic work of the path (see attention_plus_scoring_frac)"))
+    for name in ("select", "merge", "move"):
+        if name in kern:
+            b = main_res["hbm_bytes_per_step"][name]
+            rooflines.append(entry(name, "hbm", b / (kern[name]["ms_per_step"] * 1e-3) / 1e9, "GB/s",
+                                   "bytes_per_launch", round(b / kern[name]["launches_per_step"], 1),
+                                   "bytes from this run's own counts (compaction_totals_per_step)"))
+    dec = main_res["decode_step"]
+    if dec:
+        e = {"kernel": "decode", "bound": "hbm", "achieved": dec["GBps_on_device"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": round(dec["GBps_on_device"] / PEAK_HBM_GBS, 4), "avg_launch_us": dec["us_per_layer_on_device"],
+             "bytes_per_launch": dec["bytes_per_layer"]}
+        if peaks:
+            e["frac_of_attainable"] = round(dec["GBps_on_device"] / peaks["hbm_copy_GBps"], 4)
+        rooflines.append(e)
+    compact_us = sum(kern[k]["ms_per_step"] for k in ("select", "merge", "move") if k in kern) * 1e3
+    compact_bytes = sum(main_res["hbm_bytes_per_step"].values())
     line = {
         "metric": "prefill tokens/s at fixed KV budget (1 GPU)",
         "value": round(main_res["tokens_per_s"], 1),
@@ -327,6 +455,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(main_res["ms_per_step"], 4),
+        "ms_per_step_median_hip_events": round(main_res["ms_per_step_median_hip_events"], 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -346,11 +475,23 @@ def main():
             "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
             "traffic": ATTENTION_TRAFFIC_BYTES.get(wl.name),
+            "traffic_source": "stored figure from the rocprofv3 --pmc runs summarised under profiles/ "
+                              "(FETCH_SIZE and WRITE_SIZE scaled by a plain copy); not measured by this run",
             "avg_launch_us": round(att["avg_us"], 2),
             "flops_per_launch": main_res["attention_flops_per_launch"],
             "attention_plus_scoring_tflops": round(main_res["attention_plus_scoring_tflops"], 2),
             "attention_plus_scoring_frac": round(main_res["attention_plus_scoring_tflops"] / PEAK_BF16_TFLOPS, 4),
+            "frac_of_attainable": round(achieved / peaks["mfma_bf16_tflops"], 4) if peaks else None,
         },
+        "rooflines": rooflines,
+        "select_merge_move": {
+            "us_per_evicting_layer_block": round(compact_us / max(1.0, kern["select"]["launches_per_step"] * kern["select"]["layers_per_launch"]), 2) if "select" in kern else None,
+            "layers_per_launch": kern["select"]["layers_per_launch"] if "select" in kern else None,
+            "GBps": round(compact_bytes / (compact_us * 1e-6) / 1e9, 1) if compact_us else None,
+            "frac_of_hbm_peak": round(compact_bytes / (compact_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4) if compact_us else None,
+        },
+        "attainable": peaks,
+        "compaction_totals_per_step": main_res["compaction_totals_per_step"],
         "kernels": {k: {kk: round(vv, 3) for kk, vv in v.items()} for k, v in main_res["kernels"].items()},
         "profiled_ms_per_step": round(main_res["profiled_ms_per_step"], 4),
         "peak_kv_bytes": {

@@ -255,6 +255,13 @@ int kvp_set_state(kvp_cache* cache, int32_t layer, int32_t count, int32_t next_t
  * rounding; only speed differs.  KVP_EINVAL for any other value. */
 int kvp_set_attention_shape(kvp_cache* cache, int32_t shape);
 
+/* Tuning and test aid: where kvp_prefill_chunk takes the scores of Eq. 4 from.
+ * 1 (the default): the attention launch itself sweeps its keys a second time once
+ * its rows have their normalisers; 0: a separate column-sum kernel after it.  The
+ * scores agree to rounding (different summation orders).  Configurations with more
+ * than 64 workgroups per KV head always use the separate kernel. */
+int kvp_set_score_sweep(kvp_cache* cache, int32_t fused);
+
 /* Inspection of the last block of a layer (device pointers, valid until the
  * layer's scratch set is reused).  n_cand = c + n of that block; candidates are
  * cache slots 0..c-1 then block tokens.
@@ -267,6 +274,20 @@ int kvp_set_attention_shape(kvp_cache* cache, int32_t shape);
 int kvp_debug_last(kvp_cache* cache, int32_t layer, const float** scores, const uint8_t** keep,
                    const int32_t** dst, int32_t* n_cand, int32_t* stride);
 
+/* Running totals of what the compactions of this cache have done since
+ * kvp_init_cache, kept on the device (a measurement aid: the benchmark turns
+ * them into the bytes the compaction kernels had to move).  *totals receives a
+ * DEVICE pointer to KVP_T_COUNT unsigned 64-bit counters (NULL for a dry-run
+ * cache); read them after synchronising with the streams in use. */
+enum {
+  KVP_T_EVICTING_HEADS = 0,       /* (layer, KV head) compactions that had to evict          */
+  KVP_T_MOVED_ROWS = 1,           /* kept block tokens copied into freed slots (K and V each) */
+  KVP_T_MERGE_DESTINATIONS = 2,   /* rows rewritten as a weighted mean                        */
+  KVP_T_MERGE_SOURCES = 3,        /* evicted rows averaged into a destination                 */
+  KVP_T_COUNT = 4
+};
+int kvp_debug_totals(kvp_cache* cache, const uint64_t** totals);
+
 /* Per-kernel timing with HIP events on the launching stream.  While enabled
  * every launch is bracketed by two events.  kvp_profile_read waits for the
  * recorded events, adds them up per kernel kind and clears them. */
@@ -276,11 +297,25 @@ enum {
 };
 typedef struct kvp_kernel_stat {
   int64_t launches;
+  int64_t layers;     /* layers those launches covered: kvp_prefill_block compacts a group of
+                         layers with one launch of each kernel */
   double total_ms;
 } kvp_kernel_stat;
 int kvp_profile_enable(kvp_cache* cache, int32_t on);
 int kvp_profile_read(kvp_cache* cache, kvp_kernel_stat* stats /* [KVP_K_COUNT] */);
 const char* kvp_kernel_name(int32_t kind);
+
+/* Measurement aids: what this GPU attains, next to the published peaks.
+ * kvp_probe_mfma enqueues `workgroups` workgroups of eight waves that each issue
+ * 16 * iters dense 32x32x16 bf16 matrix instructions on register operands (no
+ * memory traffic) and leave a checksum per thread in device_out (workgroups *
+ * 512 floats); *flops (host) receives the flops of the launch.  kvp_probe_copy
+ * enqueues a plain device copy of `bytes` (a multiple of 16, both pointers
+ * 16-byte aligned) on `workgroups` workgroups of 256 threads.  The caller times
+ * them with events on `stream`.  Neither needs a cache. */
+int kvp_probe_mfma(void* device_out, size_t out_bytes, int32_t workgroups, int32_t iters, void* stream,
+                   double* flops);
+int kvp_probe_copy(void* device_dst, const void* device_src, size_t bytes, int32_t workgroups, void* stream);
 
 void kvp_free_cache(kvp_cache* cache);   /* host object only; NULL is fine */
 

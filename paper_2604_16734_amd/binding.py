@@ -43,7 +43,7 @@ class KvpView(ctypes.Structure):
 
 
 class KvpKernelStat(ctypes.Structure):
-    _fields_ = [("launches", ctypes.c_int64), ("total_ms", ctypes.c_double)]
+    _fields_ = [("launches", ctypes.c_int64), ("layers", ctypes.c_int64), ("total_ms", ctypes.c_double)]
 
 
 _lib = None
@@ -103,12 +103,20 @@ def lib():
         L.kvp_set_state.argtypes = [vp, i32, i32, i32]
         L.kvp_set_attention_shape.restype = ctypes.c_int
         L.kvp_set_attention_shape.argtypes = [vp, i32]
+        L.kvp_set_score_sweep.restype = ctypes.c_int
+        L.kvp_set_score_sweep.argtypes = [vp, i32]
         L.kvp_debug_last.restype = ctypes.c_int
         L.kvp_debug_last.argtypes = [vp, i32, P(vp), P(vp), P(vp), P(i32), P(i32)]
+        L.kvp_debug_totals.restype = ctypes.c_int
+        L.kvp_debug_totals.argtypes = [vp, P(vp)]
         L.kvp_profile_enable.restype = ctypes.c_int
         L.kvp_profile_enable.argtypes = [vp, i32]
         L.kvp_profile_read.restype = ctypes.c_int
         L.kvp_profile_read.argtypes = [vp, P(KvpKernelStat)]
+        L.kvp_probe_mfma.restype = ctypes.c_int
+        L.kvp_probe_mfma.argtypes = [vp, sz, i32, i32, vp, P(ctypes.c_double)]
+        L.kvp_probe_copy.restype = ctypes.c_int
+        L.kvp_probe_copy.argtypes = [vp, vp, sz, i32, vp]
         L.kvp_free_cache.restype = None
         L.kvp_free_cache.argtypes = [vp]
         _lib = L
@@ -210,6 +218,10 @@ def kvp_set_attention_shape(handle, shape):
     return lib().kvp_set_attention_shape(handle, shape)
 
 
+def kvp_set_score_sweep(handle, fused):
+    return lib().kvp_set_score_sweep(handle, int(fused))
+
+
 def kvp_debug_last(handle, layer):
     """Returns (code, scores_ptr, keep_ptr, dst_ptr, n_cand, stride)."""
     s, k, d = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
@@ -219,15 +231,36 @@ def kvp_debug_last(handle, layer):
     return rc, s.value, k.value, d.value, n.value, st.value
 
 
+TOTALS = ("evicting_heads", "moved_rows", "merge_destinations", "merge_sources")
+
+
+def kvp_debug_totals(handle):
+    """Returns (code, device pointer to len(TOTALS) uint64 counters)."""
+    p = ctypes.c_void_p()
+    rc = lib().kvp_debug_totals(handle, ctypes.byref(p))
+    return rc, p.value
+
+
 def kvp_profile_enable(handle, on):
     return lib().kvp_profile_enable(handle, int(on))
 
 
 def kvp_profile_read(handle):
-    """Returns (code, {kernel name: (launches, total_ms)})."""
+    """Returns (code, {kernel name: (launches, total_ms, layers covered)})."""
     arr = (KvpKernelStat * len(KERNEL_KINDS))()
     rc = lib().kvp_profile_read(handle, arr)
-    return rc, {name: (arr[i].launches, arr[i].total_ms) for i, name in enumerate(KERNEL_KINDS)}
+    return rc, {name: (arr[i].launches, arr[i].total_ms, arr[i].layers) for i, name in enumerate(KERNEL_KINDS)}
+
+
+def kvp_probe_mfma(device_out, out_bytes, workgroups, iters, stream=0):
+    """Returns (code, flops of the launch)."""
+    flops = ctypes.c_double()
+    rc = lib().kvp_probe_mfma(device_out, out_bytes, workgroups, iters, stream, ctypes.byref(flops))
+    return rc, flops.value
+
+
+def kvp_probe_copy(device_dst, device_src, nbytes, workgroups, stream=0):
+    return lib().kvp_probe_copy(device_dst, device_src, nbytes, workgroups, stream)
 
 
 def kvp_free_cache(handle):
@@ -398,6 +431,9 @@ class Cache:
     def set_attention_shape(self, shape):
         _check(kvp_set_attention_shape(self.handle, shape), "kvp_set_attention_shape")
 
+    def set_score_sweep(self, fused):
+        _check(kvp_set_score_sweep(self.handle, fused), "kvp_set_score_sweep")
+
     def debug_last(self, layer):
         """(scores, keep, dst) of the layer's last block, each [Hkv, n_cand]."""
         torch = self.torch
@@ -407,6 +443,14 @@ class Cache:
         return (self._view_tensor(s, (h, st), torch.float32)[:, :n],
                 self._view_tensor(k, (h, st), torch.uint8)[:, :n],
                 self._view_tensor(d, (h, st), torch.int32)[:, :n])
+
+    def totals(self):
+        """{name: count} of the compaction totals since creation (synchronises the device)."""
+        rc, p = kvp_debug_totals(self.handle)
+        _check(rc, "kvp_debug_totals")
+        self.torch.cuda.synchronize(self.device)
+        t = self._view_tensor(p, (len(TOTALS),), self.torch.int64).cpu().tolist()
+        return dict(zip(TOTALS, t))
 
     def profile_enable(self, on=True):
         _check(kvp_profile_enable(self.handle, on), "kvp_profile_enable")

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvp.so")
-SOURCES = ["attention.hip", "colsum.hip", "rowstat.hip", "keydiff.hip", "decode.hip", "select.hip", "compact.hip", "kvp.cpp"]
+SOURCES = ["attention.hip", "colsum.hip", "rowstat.hip", "keydiff.hip", "decode.hip", "select.hip", "compact.hip", "probe.hip", "plan.cpp", "kvp.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed fp32 arithmetic is kept out of the generated code on purpose
@@ -56,6 +56,22 @@ def build(verbose=False):
                 print(out)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     return LIB
+
+
+def build_host_sanitized(out_dir):
+    """The host side alone (kvp.cpp and plan.cpp; kernel launchers and HIP runtime calls stubbed) with
+    the driver of tests/host_asan, compiled by g++ with the address and undefined-behaviour
+    sanitizers.  Returns the path of the executable."""
+    rocm_inc = os.path.join(os.path.dirname(os.path.dirname(os.path.realpath(_hipcc()))), "include")
+    tests = os.path.join(ROOT, "tests", "host_asan")
+    exe = os.path.join(out_dir, "kvp_host_check")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-static-libasan", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-isystem", rocm_inc,
+           os.path.join(CSRC, "kvp.cpp"), os.path.join(CSRC, "plan.cpp"),
+           os.path.join(tests, "stubs.cpp"), os.path.join(tests, "driver.cpp"), "-o", exe]
+    _run(cmd)
+    return exe
 
 
 if __name__ == "__main__":

@@ -62,6 +62,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
@@ -113,7 +114,11 @@ struct Shape {
   static constexpr int kMergeBytes = (KS - 1) * QW * kMergeFloats * 4;
   static constexpr int kStripRow = 2 * D + 16;        // bytes of an output row staged in LDS, padded
   static constexpr int kEpilogueBytes = kMergeBytes + QW * 32 * kStripRow;
-  static constexpr int kLdsBytes = kTileBytes > kEpilogueBytes ? kTileBytes : kEpilogueBytes;
+  static constexpr int kMainBytes = kTileBytes > kEpilogueBytes ? kTileBytes : kEpilogueBytes;
+  // behind the tiles, for the score sweep: the finished row statistics of the workgroup's rows
+  static constexpr int kScoreBytes = QW * QT * 32 * 4;
+  static constexpr int kLdsBytes = kMainBytes + kScoreBytes;
+  static_assert(kLdsBytes <= 160 * 1024, "LDS of a CU");
   static_assert(kWaves == 4 || kWaves == 8, "four or eight waves per workgroup");
   static_assert(kTk == 128, "the staging map assumes 128-key tiles");
 };
@@ -126,6 +131,7 @@ attention_kernel(const AttnArgs a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   u16* const lds_k = reinterpret_cast<u16*>(lds_raw);              // [2][kTile]
   u16* const lds_v = lds_k + 2 * S::kTile;                         // [2][kTile]
+  float* const lse_lds = reinterpret_cast<float*>(lds_raw + S::kMainBytes);   // [QW][QT][32]
 
   // XCD-aware order: consecutive work items (same KV head) land on one die
   const int xcd = blockIdx.x % kXcds;
@@ -616,8 +622,9 @@ attention_kernel(const AttnArgs a) {
               pk.y = pack_bf16(o[tq][dt][4 * j + 2] * inv, o[tq][dt][4 * j + 3] * inv);
               *reinterpret_cast<u32x2*>(strip + l32 * S::kStripRow + 2 * (32 * dt + 8 * j + 4 * g)) = pk;
             }
-          if (g == 0 && row < n)
-            a.lse2[(size_t)h * a.lse_stride + row] = m_ref[tq] * sl2 + __builtin_log2f(l_run[tq]);
+          const float lse_row = m_ref[tq] * sl2 + __builtin_log2f(l_run[tq]);
+          if (g == 0) lse_lds[(qw * QT + tq) * 32 + l32] = lse_row;
+          if (g == 0 && row < n) a.lse2[(size_t)h * a.lse_stride + row] = lse_row;
 #pragma unroll
           for (int it = 0; it < D / 16; ++it) {
             const int idx = it * 64 + lane;
@@ -629,14 +636,13 @@ attention_kernel(const AttnArgs a) {
           }
         }
       }
-      return;
     }
   }
 
   // ================================================================ careful path
   // Textbook online softmax, one 32-row tile per wave, one tile buffer, no overlap.
   // Only reached when a logit exceeded its row's reference by more than 2^64.
-  {
+  if (redo) {
     const bool active = wave < S::kRows / 32;
     const int qs = active ? first_row_of(wave / QT) + 32 * (wave % QT) : 0;
     bf16x8 qf[D / 16];
@@ -724,7 +730,200 @@ attention_kernel(const AttnArgs a) {
         }
         if (g == 0) a.lse2[(size_t)h * a.lse_stride + row] = m_run * sl2 + __builtin_log2f(l_run);
       }
+      // wave w worked on row group w / QT, tile w % QT: the same order as the fast path's
+      if (g == 0) lse_lds[wave * 32 + l32] = m_run * sl2 + __builtin_log2f(l_run);
     }
+  }
+
+  // ================================================================ scores
+  // Eq. 4 needs every row's FINAL normaliser, so the column sums are a second sweep over the
+  // workgroup's keys, now that its rows have their log-sum-exp.  The roles change: the workgroup's
+  // query rows go into LDS once (row tiles of 32), and every wave takes every kWaves-th block of
+  // 32 keys and keeps it in registers as the B operand while the row tiles pass by as the A
+  // operand.  S = Q K^T then has one KEY column per lane and 16 rows of it in the lane's
+  // registers: exp2(S - lse) is the exact softmax weight, the column sum is a running add inside
+  // the lane, and after the last row tile the lane pair holds the sum over all of the workgroup's
+  // rows.  No barrier, no exchange between waves, no atomics: one partial array per workgroup,
+  // and the selection adds the arrays of a KV head in a fixed order.
+  if (a.partial == nullptr) return;
+  {
+    constexpr int kNK = D / 16;
+    constexpr int kRowTiles = QW * QT;
+    static_assert(kRowTiles % 2 == 0, "the two accumulator sets alternate over the row tiles");
+    __syncthreads();               // the statistics are in LDS; nobody needs the tile buffers any more
+    // ---- the workgroup's query rows, swizzled like a K tile (chunk ch of row r at ch ^ (r % kChunks)):
+    // row tile i holds rows first_row_of(i / QT) + 32 (i % QT) + 0..31, as lse_lds does
+    u16* const q_lds = lds_k;
+    for (int idx = tid; idx < kRowTiles * 32 * S::kChunks; idx += kThreads) {
+      const int ch = idx % S::kChunks, r = (idx / S::kChunks) % 32, ti = idx / (S::kChunks * 32);
+      const int row = min(first_row_of(ti / QT) + 32 * (ti % QT) + r, n - 1);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(a.q + ((size_t)row * a.n_q_heads + h) * D + 8 * ch);
+      *reinterpret_cast<u32x4*>(q_lds + (ti * 32 + r) * D + 8 * (ch ^ (r % S::kChunks))) = v;
+    }
+    // blocks of 32 keys that some row of the workgroup sees
+    const int n_kb = (min(n_cand, c + wg_rows_end + shift) + 31) / 32;
+    const int split = (h % group) * a.n_row_tiles + rt;
+    float* const part = a.partial + ((size_t)hk * a.n_partials + split) * a.cand_stride;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    auto load_keys = [&](bf16x8 (&kf)[kNK], int kbi) __attribute__((always_inline)) {
+      const int kv = min(kbi * 32 + l32, n_cand - 1);            // past the end: any real row, never stored
+      const u16* src = (kv < c ? kc + (size_t)kv * D : kn + (size_t)(kv - c) * new_stride) + 8 * g;
+#pragma unroll
+      for (int st = 0; st < kNK; ++st)
+        kf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + 16 * st));
+    };
+    // The scale behind an opaque copy for every variant of the stage below, made here, where all
+    // lanes are active: the variants then share no subexpression, and the compiler cannot lift the
+    // scale-and-shift of all sixteen elements above the branch that picks the variant, out of the
+    // MFMAs' shadow.
+    float sl2_copy[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("v_mov_b32 %0, %1" : "=v"(sl2_copy[i]) : "s"(sl2));
+    // The slot before the current one: its logits wait in the other accumulator set.
+    bool p_vis = false, p_plain = false;
+    int p_kb0 = 0, p_row0 = 0, p_tile = 0;
+
+    // One slot: the MFMAs of (key block, row tile) into s_new among the exponentials of the slot
+    // before it from s_exp, laid out MFMA by MFMA as in the first sweep.  Returns this lane's sum
+    // of the exponentiated slot over its 16 rows.
+    auto stage = [&](const f32x16& s_exp, f32x16& s_new, const u16* qt, const bf16x8 (&kf)[kNK], auto do_mfma,
+                     auto do_exp, auto mask) __attribute__((always_inline)) -> float {
+      constexpr bool kMfma = decltype(do_mfma)::value, kExp = decltype(do_exp)::value, kMask = decltype(mask)::value;
+      constexpr int kPer = kMfma ? 16 / kNK : 16;
+      constexpr int kAhead = kNK < 4 ? kNK : 4;
+      bf16x8 qfr[kNK];
+      float ls[16];
+      float sum[2] = {0.f, 0.f};
+      int first = 0;
+      unsigned span = 0;
+      if constexpr (kExp) {
+        // statistics of the previous slot's rows: register r is row 8 (r / 4) + 4 g + r % 4 of its tile
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(&lse_lds[p_tile * 32 + 8 * j + 4 * g]);
+          ls[4 * j] = v[0]; ls[4 * j + 1] = v[1]; ls[4 * j + 2] = v[2]; ls[4 * j + 3] = v[3];
+        }
+        if constexpr (kMask) {
+          // key p_kb0 + l32 counts for the row at offset off = 8 (r / 4) + r % 4 from p_row0 + 4 g
+          // iff first <= off < rows left in the block
+          const int row0 = p_row0 + 4 * g;
+          first = p_kb0 + l32 - c - shift - row0;                 // negative for a cached key
+          span = (unsigned)max(n - row0 - first, 0);
+        }
+      }
+      const float sl2_here = sl2_copy[(kMfma ? 0 : 2) + (kMask ? 1 : 0)];
+      int ei = 0;
+      float arg = 0.f, pe1 = 0.f;
+      if constexpr (kExp) arg = __builtin_fmaf(s_exp[0], sl2_here, -ls[0]);
+      auto finish_element = [&](int e) __attribute__((always_inline)) {      // element e is in pe1
+        float p = pe1;
+        if constexpr (kMask) p = (unsigned)(8 * (e >> 2) + (e & 3) - first) < span ? p : 0.f;
+        sum[e & 1] += p;
+        asm volatile("" : "+v"(sum[e & 1]));
+      };
+      auto exp_some = [&]() __attribute__((always_inline)) {
+        if constexpr (kExp) {
+#pragma unroll
+          for (int k = 0; k < kPer; ++k, ++ei) {
+            const float pe = __builtin_amdgcn_exp2f(arg);
+            if (ei + 1 < 16) arg = __builtin_fmaf(s_exp[ei + 1], sl2_here, -ls[ei + 1]);
+            if (ei >= 1) finish_element(ei - 1);
+            pe1 = pe;
+          }
+        }
+      };
+      if constexpr (kMfma) {
+#pragma unroll
+        for (int st = 0; st < kAhead; ++st) qfr[st] = lds_read_b128(qt + k_off[st]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < kNK; ++st) {
+          if (st + kAhead < kNK) qfr[st + kAhead] = lds_read_b128(qt + k_off[st + kAhead]);
+          s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[st], kf[st], st == 0 ? zero : s_new, 0, 0, 0);
+          exp_some();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+        exp_some();
+      }
+      if constexpr (kExp) finish_element(15);
+      if constexpr (kMfma) {
+        // A vector instruction may read the result of a 32x32x16 matrix instruction only twelve wait
+        // states after it was issued.  The next reader of s_new sits in another basic block (the next
+        // slot's variant, or a register copy the compiler puts at a block boundary), and measured
+        // results show that nobody counts the distance across that boundary: a slot that consists
+        // of matrix instructions only was read too early.  So every slot pays the distance itself.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 7\n\ts_nop 3");
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      return sum[0] + sum[1];
+    };
+    typedef std::true_type Yes;
+    typedef std::false_type No;
+    // the slot as it stands: is the current pair visible at all, was the previous one, did it need the mask
+    auto slot = [&](const f32x16& s_exp, f32x16& s_new, const u16* qt, const bf16x8 (&kf)[kNK], bool vis)
+        __attribute__((always_inline)) -> float {
+      if (vis) {
+        if (!p_vis) return stage(s_exp, s_new, qt, kf, Yes{}, No{}, No{});
+        return p_plain ? stage(s_exp, s_new, qt, kf, Yes{}, Yes{}, No{}) : stage(s_exp, s_new, qt, kf, Yes{}, Yes{}, Yes{});
+      }
+      if (!p_vis) return 0.f;
+      return p_plain ? stage(s_exp, s_new, qt, kf, No{}, Yes{}, No{}) : stage(s_exp, s_new, qt, kf, No{}, Yes{}, Yes{});
+    };
+    auto store_block = [&](int kbi, float mine) __attribute__((always_inline)) {
+      const float tot = sum_with_other_half(mine);       // lanes l and l + 32 hold the two halves of the rows
+      const int kv = kbi * 32 + l32;
+      if (g == 0 && kv < n_cand) part[kv] = tot;
+    };
+
+    f32x16 sa = zero, sb = zero;
+    float carry = 0.f;             // sums of the block before the current one, its last slot still to come
+    int carry_kb = -1;
+    // all row tiles against one key block; the next block of this wave is fetched meanwhile
+    auto do_block = [&](const bf16x8 (&kf)[kNK], int kbi) __attribute__((always_inline)) {
+      const int kb0 = kbi * 32;
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < kRowTiles; ++i) {
+        const int row0 = first_row_of(i / QT) + 32 * (i % QT);
+        // some row of the tile sees some key of the block; every row sees every key and all are real
+        const bool vis = row0 < n && (kb0 < c || kb0 - c <= row0 + 31 + shift);
+        const bool plain = kb0 + 31 < n_cand && (kb0 + 31 < c || kb0 + 31 - c <= row0 + shift) && row0 + 32 <= n;
+        const float got = (i & 1) ? slot(sa, sb, q_lds + i * 32 * D, kf, vis) : slot(sb, sa, q_lds + i * 32 * D, kf, vis);
+        if (i == 0) {
+          if (carry_kb >= 0) store_block(carry_kb, carry + got);   // the last slot of the block before
+        } else {
+          acc += got;
+        }
+        p_vis = vis; p_plain = plain; p_kb0 = kb0; p_row0 = row0; p_tile = i;
+      }
+      carry = acc;
+      carry_kb = kbi;
+    };
+    // This wave's key blocks are wave, wave + kWaves, ...; two register sets take turns, the block
+    // after the current one is on its way while the current one is worked on.  The fetches are
+    // unconditional (past the wave's last block they read it again): the compiler counts the loads
+    // in flight to place its waits, and a fetch that may or may not have been issued would make it
+    // wait for the newest one.
+    bf16x8 kfa[kNK], kfb[kNK];
+    const int last_kb = max(n_kb - 1, 0);
+    load_keys(kfa, min(wave_s, last_kb));
+    __syncthreads();               // the query rows are in LDS
+    for (int kbi = wave_s; kbi < n_kb; kbi += 2 * S::kWaves) {
+      load_keys(kfb, min(kbi + S::kWaves, last_kb));
+      do_block(kfa, kbi);
+      load_keys(kfa, min(kbi + 2 * S::kWaves, last_kb));
+      if (kbi + S::kWaves < n_kb) do_block(kfb, kbi + S::kWaves);
+    }
+    if (carry_kb >= 0) {
+      // the last slot of the last block: its logits are in the second accumulator set
+      const float got = slot(sb, sa, q_lds, kfa, false);
+      store_block(carry_kb, carry + got);
+    }
+    // keys that none of this workgroup's rows see: zeros (the selection adds every partial array)
+    for (int kv = n_kb * 32 + tid; kv < n_cand; kv += kThreads) part[kv] = 0.f;
   }
 }
 
@@ -742,8 +941,6 @@ hipError_t prepare_shape() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, Shape<D, QT, QW, KS>::kLdsBytes);
 }
 
-constexpr int kRowsOfVariant[3] = {128, 64, 128};
-
 }  // namespace
 
 // Every shape needs more dynamic LDS than a kernel gets by default.  The attribute belongs to the
@@ -756,18 +953,6 @@ hipError_t prepare_attention() {
   if ((e = prepare_shape<64, 2, 2, 2>()) != hipSuccess) return e;
   if ((e = prepare_shape<64, 1, 4, 2>()) != hipSuccess) return e;
   return prepare_shape<64, 1, 2, 2>();
-}
-
-void plan_attention(AttnArgs& a, int /*head_dim*/, int forced_shape) {
-  auto wgs = [&](int rows) { return ((a.n + rows - 1) / rows) * a.n_q_heads; };
-  // eight waves x 32 rows (two waves per SIMD) when 128-row workgroups fill the chip,
-  // otherwise four waves x 32 rows over 64-row workgroups
-  a.variant = wgs(128) >= 192 ? 2 : 1;
-  if (forced_shape >= 0 && forced_shape <= 2) a.variant = forced_shape;      // kvp_set_attention_shape
-  const int rows = kRowsOfVariant[a.variant];
-  a.n_row_tiles = (a.n + rows - 1) / rows;
-  a.total_work = a.n_row_tiles * a.n_q_heads;
-  a.work_per_xcd = (a.total_work + kXcds - 1) / kXcds;
 }
 
 hipError_t launch_attention(const AttnArgs& a, int head_dim, hipStream_t s) {

@@ -48,7 +48,6 @@ namespace {
 
 constexpr int kRing = 4;               // LDS query-tile buffers: the pair of tiles in use and the pair in flight
 constexpr int kStatRing = 8;           // row statistics stay one step longer than their tile: a longer ring
-constexpr int kMaxRowSplits = 16;
 
 // W waves per workgroup, NT 32-key subtiles per wave: a wave owns 32 NT keys, a workgroup 32 NT W
 template <int D, int NT, int W>
@@ -329,58 +328,17 @@ colsum_kernel(const ColsumArgs a) {
   }
 }
 
-constexpr int kWavesPerWg = 4;
-constexpr int kTargetWorkgroups = 512;     // two per CU, all resident: the launch is a single round
-
 }  // namespace
-
-int colsum_max_partials(int /*group*/, int /*chunk_max*/) { return kMaxRowSplits; }
-
-void plan_colsum(ColsumArgs& a, int /*head_dim*/) {
-  const int n_cand = a.c + a.n_keys;
-  const int n_qt = (a.n + 31) / 32;
-  // 64 keys per wave, or 32 when that is what it takes to spread a small launch over the chip
-  int nt = 2;
-  {
-    const int blocks = (n_cand + 64 * kWavesPerWg - 1) / (64 * kWavesPerWg);
-    const int splits = n_qt < kMaxRowSplits ? n_qt : kMaxRowSplits;
-    if (a.n_kv_heads * blocks * splits < kTargetWorkgroups / 2) nt = 1;
-  }
-  a.subtiles = nt;
-  const int block_keys = 32 * nt * kWavesPerWg;
-  a.n_kv_blocks = (n_cand + block_keys - 1) / block_keys;
-  // tiles per workgroup: the fewest that keep the launch within one round (and the row splits of
-  // a block within the partial count)
-  int tau = (n_qt + kMaxRowSplits - 1) / kMaxRowSplits;
-  for (;; ++tau) {
-    int total = 0, most = 0;
-    for (int k = 0; k < a.n_kv_blocks; ++k) {
-      const int blk0 = k * block_keys;
-      const int first_tile = blk0 - a.c > a.shift ? (blk0 - a.c - a.shift) / 32 : 0;
-      const int visible = n_qt - first_tile > 0 ? n_qt - first_tile : 1;
-      const int splits = (visible + tau - 1) / tau;
-      a.split_prefix[k] = total;
-      total += splits;
-      most = splits > most ? splits : most;
-    }
-    a.split_prefix[a.n_kv_blocks] = total;
-    a.wgs_per_head = total;
-    a.n_partials = most;
-    if (total * a.n_kv_heads <= kTargetWorkgroups || tau >= n_qt) break;
-  }
-  a.total_work = a.wgs_per_head * a.n_kv_heads;
-  a.work_per_xcd = (a.total_work + kXcds - 1) / kXcds;
-}
 
 hipError_t launch_colsum(const ColsumArgs& a, int head_dim, hipStream_t s) {
   const int grid = kXcds * a.work_per_xcd;
-  const dim3 g(grid), b(64 * kWavesPerWg);
+  const dim3 g(grid), b(64 * kColsumWaves);
   if (head_dim == 128) {
-    if (a.subtiles == 2) hipLaunchKernelGGL((colsum_kernel<128, 2, kWavesPerWg>), g, b, 0, s, a);
-    else hipLaunchKernelGGL((colsum_kernel<128, 1, kWavesPerWg>), g, b, 0, s, a);
+    if (a.subtiles == 2) hipLaunchKernelGGL((colsum_kernel<128, 2, kColsumWaves>), g, b, 0, s, a);
+    else hipLaunchKernelGGL((colsum_kernel<128, 1, kColsumWaves>), g, b, 0, s, a);
   } else {
-    if (a.subtiles == 2) hipLaunchKernelGGL((colsum_kernel<64, 2, kWavesPerWg>), g, b, 0, s, a);
-    else hipLaunchKernelGGL((colsum_kernel<64, 1, kWavesPerWg>), g, b, 0, s, a);
+    if (a.subtiles == 2) hipLaunchKernelGGL((colsum_kernel<64, 2, kColsumWaves>), g, b, 0, s, a);
+    else hipLaunchKernelGGL((colsum_kernel<64, 1, kColsumWaves>), g, b, 0, s, a);
   }
   return hipGetLastError();
 }

@@ -13,7 +13,9 @@
 //                 slot's token index and weight are set.  Kept cache rows never
 //                 move.  With `identity` it is the plain append of a block to a
 //                 cache that is not full.
-// One wave per row pair: lanes 0-31 carry the K row, lanes 32-63 the V row.
+// A row pair (the K row and the V row of one slot) is carried by 2 D / 8 lanes, 16 bytes each:
+// 32 lanes at head dimension 128 (two pairs per wave), 16 at 64 (four pairs per wave).  A launch
+// covers a group of layers: grid (row blocks, KV heads, layers).
 #include "kvp_internal.h"
 
 namespace kvp {
@@ -23,8 +25,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kRowsPerBlock = kThreads / 64;
+constexpr int kThreads = kCompactThreads;
 
 __device__ __forceinline__ float bf16_lo(unsigned x) { return __uint_as_float(x << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x & 0xFFFF0000u); }
@@ -34,54 +35,44 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned, b);
 }
 
-// W words of 2 bf16 per lane: head_dim = 64 W
-template <int W>
-struct Row {
-  unsigned w[W];
+template <int D>
+struct Lanes {
+  static constexpr int kPerRow = D / 8;               // 16-byte pieces of a row
+  static constexpr int kPerPair = 2 * kPerRow;        // K row then V row
+  static constexpr int kPairsPerBlock = kThreads / kPerPair;
 };
 
-template <int W>
-__device__ __forceinline__ Row<W> load_row(const u16* p, int l32) {
-  Row<W> r;
-  if (W == 2) {
-    const uint2 x = *reinterpret_cast<const uint2*>(p + 4 * l32);
-    r.w[0] = x.x; r.w[W - 1] = x.y;
-  } else {
-    r.w[0] = *reinterpret_cast<const unsigned*>(p + 2 * l32);
-  }
-  return r;
-}
-template <int W>
-__device__ __forceinline__ void store_row(u16* p, int l32, const Row<W>& r) {
-  if (W == 2) {
-    *reinterpret_cast<uint2*>(p + 4 * l32) = make_uint2(r.w[0], r.w[W - 1]);
-  } else {
-    *reinterpret_cast<unsigned*>(p + 2 * l32) = r.w[0];
-  }
+// the same pointer in scratch set (first_set + li) % n_sets instead of set first_set
+template <class T>
+__device__ __forceinline__ T* in_set_of(T* p, const LayerGroup& g, int li) {
+  const long long sets = (long long)((g.first_set + li) % g.n_sets) - g.first_set;
+  return reinterpret_cast<T*>(reinterpret_cast<uintptr_t>(p) + (uintptr_t)(sets * g.set_stride));
 }
 
-template <int W>
+template <int D>
 __global__ void __launch_bounds__(kThreads)
 merge_kernel(const CompactArgs a) {
-  constexpr int D = 64 * W;
-  const int hk = blockIdx.y;
-  const int j = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
-  if (j >= a.counts[hk].n_dst) return;
-  const int lane = threadIdx.x & 63, l32 = lane & 31;
-  const bool is_v = lane >= 32;
-  const DstEntry e = a.dsts[(size_t)hk * a.chunk_max + j];
+  using L = Lanes<D>;
+  const int hk = blockIdx.y, li = blockIdx.z;
+  const int j = blockIdx.x * L::kPairsPerBlock + threadIdx.x / L::kPerPair;
+  const HeadCounts* counts = in_set_of(a.counts, a.g, li);
+  if (j >= counts[hk].n_dst) return;
+  const int sub = threadIdx.x % L::kPerPair;
+  const bool is_v = sub >= L::kPerRow;
+  const int piece = sub % L::kPerRow;
+  const DstEntry e = in_set_of(a.dsts, a.g, li)[(size_t)hk * a.chunk_max + j];
 
-  u16* cache = (is_v ? a.v_cache : a.k_cache) + (size_t)hk * a.budget * D;
-  const u16* fresh = (is_v ? a.v_new : a.k_new) + (size_t)hk * D;
+  u16* cache = (is_v ? a.v_cache : a.k_cache) + (long long)li * a.g.kv_stride + (size_t)hk * a.budget * D;
+  const u16* fresh = (is_v ? a.g.v_new[li] : a.g.k_new[li]) + (size_t)hk * D;
   const size_t fresh_stride = (size_t)a.n_kv_heads * D;
-  const float* wts = a.weight + (size_t)hk * a.budget;
+  float* wts = a.weight + (long long)li * a.g.meta_stride + (size_t)hk * a.budget;
   auto row_of = [&](int pos) -> const u16* {
     return pos < a.c ? cache + (size_t)pos * D : fresh + (size_t)(pos - a.c) * fresh_stride;
   };
   auto weight_of = [&](int pos) -> float { return pos < a.c ? wts[pos] : 1.f; };
 
-  // fetch the destination and all (at most six) sources at once, then add them up in order
-  // sources arrive in no particular order: sort them by candidate position (unused slots last)
+  // fetch the destination and all (at most six) sources at once, then add them up in order.
+  // Sources arrive in no particular order: sort them by candidate position (unused slots last)
   // so that the fp32 sum below is taken in one fixed order
   int pos[kNeighbours + 1];
   pos[0] = e.pos;
@@ -95,77 +86,91 @@ merge_kernel(const CompactArgs a) {
       pos[k] = lo; pos[k + 1] = hi;
     }
   float wt[kNeighbours + 1];
-  Row<W> rows[kNeighbours + 1];
+  uint4 rows[kNeighbours + 1];
 #pragma unroll
   for (int k = 0; k <= kNeighbours; ++k) {
     const bool on = k <= e.n_src;
     const int pk = on ? pos[k] : e.pos;          // an unused entry re-reads the destination, weight 0
     wt[k] = on ? weight_of(pk) : 0.f;
-    rows[k] = load_row<W>(row_of(pk), l32);
+    rows[k] = *reinterpret_cast<const uint4*>(row_of(pk) + 8 * piece);
   }
   float total = wt[0];
-  float acc[2 * W];
+  float acc[8];
+  {
+    const unsigned w[4] = {rows[0].x, rows[0].y, rows[0].z, rows[0].w};
 #pragma unroll
-  for (int k = 0; k < W; ++k) {
-    acc[2 * k] = wt[0] * bf16_lo(rows[0].w[k]);
-    acc[2 * k + 1] = wt[0] * bf16_hi(rows[0].w[k]);
+    for (int k = 0; k < 4; ++k) {
+      acc[2 * k] = wt[0] * bf16_lo(w[k]);
+      acc[2 * k + 1] = wt[0] * bf16_hi(w[k]);
+    }
   }
 #pragma unroll
   for (int s = 1; s <= kNeighbours; ++s) {
     total += wt[s];
+    const unsigned w[4] = {rows[s].x, rows[s].y, rows[s].z, rows[s].w};
 #pragma unroll
-    for (int k = 0; k < W; ++k) {
-      acc[2 * k] = __builtin_fmaf(wt[s], bf16_lo(rows[s].w[k]), acc[2 * k]);
-      acc[2 * k + 1] = __builtin_fmaf(wt[s], bf16_hi(rows[s].w[k]), acc[2 * k + 1]);
+    for (int k = 0; k < 4; ++k) {
+      acc[2 * k] = __builtin_fmaf(wt[s], bf16_lo(w[k]), acc[2 * k]);
+      acc[2 * k + 1] = __builtin_fmaf(wt[s], bf16_hi(w[k]), acc[2 * k + 1]);
     }
   }
-  Row<W> res;
-#pragma unroll
-  for (int k = 0; k < W; ++k) res.w[k] = pack_bf16(acc[2 * k] / total, acc[2 * k + 1] / total);
+  uint4 res;
+  res.x = pack_bf16(acc[0] / total, acc[1] / total);
+  res.y = pack_bf16(acc[2] / total, acc[3] / total);
+  res.z = pack_bf16(acc[4] / total, acc[5] / total);
+  res.w = pack_bf16(acc[6] / total, acc[7] / total);
 
   if (e.pos < a.c) {
-    store_row<W>(cache + (size_t)e.pos * D, l32, res);
-    if (lane == 0) a.weight[(size_t)hk * a.budget + e.pos] = total;
+    *reinterpret_cast<uint4*>(cache + (size_t)e.pos * D + 8 * piece) = res;
+    if (sub == 0) wts[e.pos] = total;
   } else {
-    u16* st = (is_v ? a.stage_v : a.stage_k) + ((size_t)hk * a.chunk_max + j) * D;
-    store_row<W>(st, l32, res);
-    if (lane == 0) a.stage_w[(size_t)hk * a.chunk_max + j] = total;
+    u16* st = in_set_of(is_v ? a.stage_v : a.stage_k, a.g, li) + ((size_t)hk * a.chunk_max + j) * D;
+    *reinterpret_cast<uint4*>(st + 8 * piece) = res;
+    if (sub == 0) in_set_of(a.stage_w, a.g, li)[(size_t)hk * a.chunk_max + j] = total;
   }
 }
 
-template <int W>
+// kIdentity: the plain append of all n block tokens to slots c .. c + n - 1 (a compile-time switch:
+// chosen at run time, the two sources of the row count, a kernel argument and a device array, make
+// the compiler keep the arguments in memory)
+template <int D, bool kIdentity>
 __global__ void __launch_bounds__(kThreads)
 move_kernel(const CompactArgs a) {
-  constexpr int D = 64 * W;
-  const int hk = blockIdx.y;
-  const int i = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
-  const int count = a.identity ? a.n : a.counts[hk].n_moves;
-  if (i >= count) return;
-  const int lane = threadIdx.x & 63, l32 = lane & 31;
-  const bool is_v = lane >= 32;
+  using L = Lanes<D>;
+  const int hk = blockIdx.y, li = blockIdx.z;
+  const int i = blockIdx.x * L::kPairsPerBlock + threadIdx.x / L::kPerPair;
+  const int sub = threadIdx.x % L::kPerPair;
+  const bool is_v = sub >= L::kPerRow;
+  const int piece = sub % L::kPerRow;
   int pos, slot, stage;
-  if (a.identity) {
+  if constexpr (kIdentity) {
+    if (i >= a.n) return;
     pos = a.c + i; slot = a.c + i; stage = -1;
   } else {
-    const MoveEntry e = a.moves[(size_t)hk * a.chunk_max + i];
+    if (i >= in_set_of(a.counts, a.g, li)[hk].n_moves) return;
+    const MoveEntry e = in_set_of(a.moves, a.g, li)[(size_t)hk * a.chunk_max + i];
     pos = e.pos; slot = e.slot; stage = e.stage;
   }
-  const u16* src;
-  if (stage >= 0)
-    src = (is_v ? a.stage_v : a.stage_k) + ((size_t)hk * a.chunk_max + stage) * D;
-  else
-    src = (is_v ? a.v_new : a.k_new) + ((size_t)(pos - a.c) * a.n_kv_heads + hk) * D;
-  u16* dstp = (is_v ? a.v_cache : a.k_cache) + ((size_t)hk * a.budget + slot) * D;
-  store_row<W>(dstp, l32, load_row<W>(src, l32));
-  if (lane == 0) {
-    a.token_idx[(size_t)hk * a.budget + slot] = a.t0 + (pos - a.c);
-    a.weight[(size_t)hk * a.budget + slot] = stage >= 0 ? a.stage_w[(size_t)hk * a.chunk_max + stage] : 1.f;
+  // (both candidates are formed outside the branch: they come from the kernel arguments, and a load
+  // of an argument whose address depends on a per-lane condition would push the arguments to memory)
+  const u16* const k_new = a.g.k_new[li];
+  const u16* const v_new = a.g.v_new[li];
+  const u16* const staged = in_set_of(is_v ? a.stage_v : a.stage_k, a.g, li) + ((size_t)hk * a.chunk_max + max(stage, 0)) * D;
+  const u16* const fresh = (is_v ? v_new : k_new) + ((size_t)(pos - a.c) * a.n_kv_heads + hk) * D;
+  const u16* const src = stage >= 0 ? staged : fresh;
+  u16* dstp = (is_v ? a.v_cache : a.k_cache) + (long long)li * a.g.kv_stride + ((size_t)hk * a.budget + slot) * D;
+  *reinterpret_cast<uint4*>(dstp + 8 * piece) = *reinterpret_cast<const uint4*>(src + 8 * piece);
+  if (sub == 0) {
+    const size_t m = (size_t)((long long)li * a.g.meta_stride) + (size_t)hk * a.budget + slot;
+    a.token_idx[m] = a.t0 + (pos - a.c);
+    a.weight[m] = stage >= 0 ? in_set_of(a.stage_w, a.g, li)[(size_t)hk * a.chunk_max + stage] : 1.f;
   }
 }
 
 struct InitArgs {
   Seg segs[KVP_MAX_SEGMENTS];
   Seg* dst;
+  unsigned long long* totals;
   int n_segs;
 };
 
@@ -176,37 +181,40 @@ __global__ void fill_kernel(int32_t* token_idx, float* weight, size_t n, InitArg
     weight[i] = 0.f;
   }
   if (i < (size_t)ia.n_segs) ia.dst[i] = ia.segs[i];
+  if (i < (size_t)KVP_T_COUNT) ia.totals[i] = 0ull;
 }
 
 }  // namespace
 
 hipError_t launch_merge(const CompactArgs& a, hipStream_t s) {
-  const dim3 grid(a.blocks_per_head, a.n_kv_heads);
+  const dim3 grid(a.blocks_per_head, a.n_kv_heads, a.g.n_layers);
   if (a.head_dim == 128)
-    hipLaunchKernelGGL(merge_kernel<2>, grid, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(merge_kernel<128>, grid, dim3(kThreads), 0, s, a);
   else
-    hipLaunchKernelGGL(merge_kernel<1>, grid, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(merge_kernel<64>, grid, dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_move(const CompactArgs& a, hipStream_t s) {
-  const dim3 grid(a.blocks_per_head, a.n_kv_heads);
-  if (a.head_dim == 128)
-    hipLaunchKernelGGL(move_kernel<2>, grid, dim3(kThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL(move_kernel<1>, grid, dim3(kThreads), 0, s, a);
+  const dim3 grid(a.blocks_per_head, a.n_kv_heads, a.g.n_layers);
+  if (a.head_dim == 128) {
+    if (a.identity) hipLaunchKernelGGL((move_kernel<128, true>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((move_kernel<128, false>), grid, dim3(kThreads), 0, s, a);
+  } else {
+    if (a.identity) hipLaunchKernelGGL((move_kernel<64, true>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((move_kernel<64, false>), grid, dim3(kThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 
-int rows_per_compact_block() { return kRowsPerBlock; }
-
 hipError_t launch_init(int32_t* token_idx, float* weight, size_t n_slots, const Seg* host_segs,
-                       int n_segs, Seg* dev_segs, hipStream_t s) {
+                       int n_segs, Seg* dev_segs, unsigned long long* totals, hipStream_t s) {
   InitArgs ia;
   for (int i = 0; i < KVP_MAX_SEGMENTS; ++i) ia.segs[i] = i < n_segs ? host_segs[i] : Seg{0, 0, 0, 0, 0, 0, 0};
   ia.dst = dev_segs;
+  ia.totals = totals;
   ia.n_segs = n_segs;
-  size_t n = n_slots > (size_t)n_segs ? n_slots : (size_t)n_segs;
+  size_t n = n_slots > (size_t)KVP_MAX_SEGMENTS ? n_slots : (size_t)KVP_MAX_SEGMENTS;
   const unsigned blocks = (unsigned)((n + 255) / 256);
   hipLaunchKernelGGL(fill_kernel, dim3(blocks), dim3(256), 0, s, token_idx, weight, n_slots, ia);
   return hipGetLastError();

@@ -32,9 +32,9 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kTile = 64;            // keys per workgroup step
-constexpr int kGroupLimit = 16;      // query heads per KV head
-constexpr int kMaxSplits = 128;
+constexpr int kTile = kDecodeTile;   // keys per workgroup step
+constexpr int kGroupLimit = kDecodeGroupLimit;   // query heads per KV head
+constexpr int kMaxSplits = kDecodeMaxSplits;
 
 __device__ __forceinline__ float bf16_lo(unsigned x) { return __uint_as_float(x << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x & 0xFFFF0000u); }
@@ -270,24 +270,6 @@ hipError_t decode_static_scratch(float** ptr, size_t* n_floats) {
   }
   *ptr = g_scratch_ptr[dev];
   return hipSuccess;
-}
-
-int decode_max_group() { return kGroupLimit; }
-
-// workgroups per KV head the step would like: one per 64-key tile, kMaxSplits at most
-int decode_splits_wanted(long long n_keys) {
-  const long long want = (n_keys + kTile - 1) / kTile;
-  return (int)(want > kMaxSplits ? kMaxSplits : want);
-}
-
-// workgroups per KV head: one per 64-key tile while the partials fit, kMaxSplits at most
-// (every workgroup then has at least one tile)
-int decode_splits(long long n_keys, int head_dim, size_t scratch_floats, int n_q_heads) {
-  long long want = (n_keys + kTile - 1) / kTile;
-  if (want > kMaxSplits) want = kMaxSplits;
-  const long long fit = (long long)(scratch_floats / ((size_t)n_q_heads * (head_dim + 2)));
-  if (want > fit) want = fit;
-  return want < 1 ? 0 : (int)want;
 }
 
 hipError_t launch_decode(const DecodeArgs& a, int head_dim, hipStream_t s) {

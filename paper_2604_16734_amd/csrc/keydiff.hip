@@ -19,7 +19,7 @@ namespace kvp {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kSliceKeys = 64;         // keys per workgroup of the sum kernel
+constexpr int kSliceKeys = kKeydiffSliceKeys;   // keys per workgroup of the sum kernel
 
 __device__ __forceinline__ const u16* key_row(const KeydiffArgs& a, int hk, int kv, int D) {
   return kv < a.c ? a.k_cache + ((size_t)hk * a.budget + kv) * D
@@ -131,8 +131,6 @@ keydiff_score_kernel(const KeydiffArgs a) {
 }
 
 }  // namespace
-
-int keydiff_slices(int n_cand) { return (n_cand + kSliceKeys - 1) / kSliceKeys; }
 
 hipError_t launch_keydiff(KeydiffArgs a, int head_dim, hipStream_t s) {
   const int n_cand = a.c + a.n_keys;

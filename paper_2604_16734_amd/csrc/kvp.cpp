@@ -24,7 +24,7 @@ struct Layout {
   size_t kv_layer_bytes, meta_layer_elems;
   size_t persistent_bytes;
   // global
-  size_t segs_off;
+  size_t segs_off, totals_off;
   // scratch, per set
   size_t set_off, set_bytes;
   size_t lse_off, partial_off, scores_off, keep_off, dst_off, counts_off, moves_off, dsts_off,
@@ -59,9 +59,17 @@ Layout make_layout(const kvp_config& c) {
   L.w_off = off; off = align_up(off + L_ * L.meta_layer_elems * 4);
   L.persistent_bytes = off;
   L.segs_off = off; off = align_up(off + KVP_MAX_SEGMENTS * sizeof(Seg));
+  L.totals_off = off; off = align_up(off + KVP_T_COUNT * sizeof(unsigned long long));
   L.n_sets = c.scratch_sets ? c.scratch_sets : 1;
   L.cand_stride = (int)((M + B + 63) / 64 * 64);
+  // partial score arrays per KV head: what the separate column-sum kernel needs, or, when the
+  // attention kernel leaves the scores itself, one per workgroup of a KV head (query heads of the
+  // group x row tiles), as long as that stays modest
   L.max_partials = colsum_max_partials(c.n_q_heads / c.n_kv_heads, c.chunk_max);
+  {
+    const int fused = attention_max_partials(c.n_q_heads / c.n_kv_heads, c.chunk_max);
+    if (fused <= kMaxFusedPartials && fused > L.max_partials) L.max_partials = fused;
+  }
   size_t s = 0;
   L.lse_off = s; s = align_up(s + (size_t)c.n_q_heads * B * 4);
   L.partial_off = s; s = align_up(s + H * L.max_partials * L.cand_stride * 4);
@@ -99,6 +107,7 @@ struct Layer {
 
 struct ProfEvent {
   int kind;
+  int layers;           // layers the launch covered
   hipEvent_t start, stop;
 };
 
@@ -115,6 +124,7 @@ struct kvp_cache {
   float scale;
   bool dry;
   int attn_shape = -1;                // kvp_set_attention_shape; < 0: chosen per launch
+  bool fused_scores = true;           // kvp_set_score_sweep: scores out of the attention launch itself
   float* static_scratch = nullptr;    // the file-scope scratch array on this cache's device
   size_t static_scratch_floats = 0;
   bool profiling = false;
@@ -133,6 +143,7 @@ struct kvp_cache {
   int32_t* idx(int l) const { return reinterpret_cast<int32_t*>(base + lay.idx_off) + (size_t)l * lay.meta_layer_elems; }
   float* weight(int l) const { return reinterpret_cast<float*>(base + lay.w_off) + (size_t)l * lay.meta_layer_elems; }
   Seg* dev_segs() const { return reinterpret_cast<Seg*>(base + lay.segs_off); }
+  unsigned long long* totals() const { return reinterpret_cast<unsigned long long*>(base + lay.totals_off); }
   unsigned char* set(int l) const { return base + lay.set_off + (size_t)(l % lay.n_sets) * lay.set_bytes; }
 };
 
@@ -140,9 +151,9 @@ namespace {
 
 // Runs one launch, bracketed by events when profiling.
 template <class F>
-int launch(kvp_cache* c, int kind, hipStream_t s, F&& f) {
+int launch(kvp_cache* c, int kind, int layers, hipStream_t s, F&& f) {
   if (c->dry) return KVP_OK;
-  ProfEvent pe{kind, nullptr, nullptr};
+  ProfEvent pe{kind, layers, nullptr, nullptr};
   if (c->profiling) {
     for (hipEvent_t* e : {&pe.start, &pe.stop}) {
       if (!c->pool.empty()) {
@@ -162,20 +173,33 @@ int launch(kvp_cache* c, int kind, hipStream_t s, F&& f) {
   return KVP_OK;
 }
 
-int run_compact(kvp_cache* c, int layer, const float* scores_override, hipStream_t s) {
-  Layer& L = c->layers[layer];
+// Alg. 1 lines 7-11 for `count` consecutive layers that hold the same block (same entries in the
+// cache, same tokens pending): one launch of each compaction kernel for all of them.
+int run_compact(kvp_cache* c, int first, int count, const float* scores_override, hipStream_t s) {
+  Layer& L = c->layers[first];
   const kvp_config& cfg = c->cfg;
   const Layout& lay = c->lay;
-  unsigned char* set = c->set(layer);
+  unsigned char* set = c->set(first);
   const int cnt = L.count, n = L.n, M = cfg.budget;
 
+  LayerGroup g{};
+  g.n_layers = count;
+  g.first_set = first % lay.n_sets;
+  g.n_sets = lay.n_sets;
+  g.set_stride = (long long)lay.set_bytes;
+  g.kv_stride = (long long)(lay.kv_layer_bytes / 2);
+  g.meta_stride = (long long)lay.meta_layer_elems;
+  for (int i = 0; i < count; ++i) {
+    g.k_new[i] = c->layers[first + i].k;
+    g.v_new[i] = c->layers[first + i].v;
+  }
+
   CompactArgs ca{};
-  ca.k_cache = c->k_cache(layer);
-  ca.v_cache = c->v_cache(layer);
-  ca.token_idx = c->idx(layer);
-  ca.weight = c->weight(layer);
-  ca.k_new = L.k;
-  ca.v_new = L.v;
+  ca.g = g;
+  ca.k_cache = c->k_cache(first);
+  ca.v_cache = c->v_cache(first);
+  ca.token_idx = c->idx(first);
+  ca.weight = c->weight(first);
   ca.counts = reinterpret_cast<HeadCounts*>(set + lay.counts_off);
   ca.moves = reinterpret_cast<MoveEntry*>(set + lay.moves_off);
   ca.dsts = reinterpret_cast<DstEntry*>(set + lay.dsts_off);
@@ -184,29 +208,28 @@ int run_compact(kvp_cache* c, int layer, const float* scores_override, hipStream
   ca.stage_w = reinterpret_cast<float*>(set + lay.stage_w_off);
   ca.c = cnt; ca.n = n; ca.t0 = L.t0; ca.budget = M;
   ca.n_kv_heads = cfg.n_kv_heads; ca.head_dim = cfg.head_dim; ca.chunk_max = cfg.chunk_max;
-  const int rpb = rows_per_compact_block();
+  const int rpb = rows_per_compact_block(cfg.head_dim);
 
   if (cnt + n <= M) {
     // Alg. 1 line 8 is false: plain append
     ca.identity = 1;
     ca.blocks_per_head = (n + rpb - 1) / rpb;
-    int rc = launch(c, KVP_K_MOVE, s, [&] { return launch_move(ca, s); });
-    if (rc) return rc;
-    L.count = cnt + n;
-    return KVP_OK;
+    return launch(c, KVP_K_MOVE, count, s, [&] { return launch_move(ca, s); });
   }
 
   SelectArgs sa{};
+  sa.g = g;
   sa.partial = scores_override ? nullptr : reinterpret_cast<const float*>(set + lay.partial_off);
   sa.score_override = scores_override;
   sa.scores = reinterpret_cast<float*>(set + lay.scores_off);
   sa.keep = set + lay.keep_off;
   sa.dst = reinterpret_cast<int32_t*>(set + lay.dst_off);
-  sa.token_idx = c->idx(layer);
+  sa.token_idx = c->idx(first);
   sa.counts = reinterpret_cast<HeadCounts*>(set + lay.counts_off);
   sa.moves = reinterpret_cast<MoveEntry*>(set + lay.moves_off);
   sa.dsts = reinterpret_cast<DstEntry*>(set + lay.dsts_off);
   sa.segs = c->dev_segs();
+  sa.totals = c->totals();
   sa.n_segs = (int)c->segs.size();
   sa.c = cnt; sa.n = n; sa.t0 = L.t0; sa.budget = M;
   sa.cand_stride = lay.cand_stride; sa.chunk_max = cfg.chunk_max;
@@ -216,7 +239,7 @@ int run_compact(kvp_cache* c, int layer, const float* scores_override, hipStream
   int ts = 2;
   while (ts < 2 * (cnt + n)) ts <<= 1;
   sa.table_size = ts;
-  int rc = launch(c, KVP_K_SELECT, s, [&] { return launch_select(sa, cfg.n_kv_heads, s); });
+  int rc = launch(c, KVP_K_SELECT, count, s, [&] { return launch_select(sa, cfg.n_kv_heads, s); });
   if (rc) return rc;
 
   ca.identity = 0;
@@ -224,13 +247,41 @@ int run_compact(kvp_cache* c, int layer, const float* scores_override, hipStream
   if (cfg.merge) {
     const int max_dst = n_evict < cfg.chunk_max ? n_evict : cfg.chunk_max;
     ca.blocks_per_head = (max_dst + rpb - 1) / rpb;
-    rc = launch(c, KVP_K_MERGE, s, [&] { return launch_merge(ca, s); });
+    rc = launch(c, KVP_K_MERGE, count, s, [&] { return launch_merge(ca, s); });
     if (rc) return rc;
   }
   ca.blocks_per_head = (n + rpb - 1) / rpb;
-  rc = launch(c, KVP_K_MOVE, s, [&] { return launch_move(ca, s); });
+  return launch(c, KVP_K_MOVE, count, s, [&] { return launch_move(ca, s); });
+}
+
+// kvp_compact for layers [first, first + count): one group launch when they hold the same block,
+// one layer at a time otherwise.  Every layer must be PENDING.
+int compact_layers(kvp_cache* c, int first, int count, const float* scores_override, hipStream_t s) {
+  for (int i = 0; i < count; ++i)
+    if (c->layers[first + i].state != PENDING) return KVP_ESTATE;
+  bool same = count <= kMaxGroupLayers && (scores_override == nullptr || count == 1);
+  const Layer& A = c->layers[first];
+  for (int i = 1; i < count && same; ++i) {
+    const Layer& B = c->layers[first + i];
+    same = B.count == A.count && B.n == A.n && B.t0 == A.t0 && B.n_partials == A.n_partials;
+  }
+  if (!same) {
+    if (scores_override != nullptr) return KVP_EINVAL;
+    for (int i = 0; i < count; ++i) {
+      const int rc = compact_layers(c, first + i, 1, nullptr, s);
+      if (rc) return rc;
+    }
+    return KVP_OK;
+  }
+  const int rc = run_compact(c, first, count, scores_override, s);
   if (rc) return rc;
-  L.count = M;
+  for (int i = 0; i < count; ++i) {
+    Layer& L = c->layers[first + i];
+    L.count = L.count + L.n <= c->cfg.budget ? L.count + L.n : c->cfg.budget;
+    L.state = READY;
+    L.next_token = L.t0 + L.n;
+    c->set_owner[(first + i) % c->lay.n_sets] = -1;
+  }
   return KVP_OK;
 }
 
@@ -317,7 +368,7 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
     if (e == hipSuccess) e = decode_static_scratch(&c->static_scratch, &c->static_scratch_floats);
     if (e == hipSuccess)
       e = launch_init(c->idx(0), c->weight(0), slots, c->segs.data(), n_segs, c->dev_segs(),
-                      static_cast<hipStream_t>(stream));
+                      c->totals(), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
       delete c;
       return KVP_EDEVICE;
@@ -367,11 +418,23 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
   aa.budget = cfg.budget; aa.lse_stride = cfg.chunk_max;
   aa.scale_log2 = c->scale * 1.4426950408889634f;
   plan_attention(aa, cfg.head_dim, c->attn_shape);
-  int rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
+  // The scores decide an eviction; a block that fits into the cache as it is needs none.  Scored
+  // by its own queries, the block's attention launch leaves the column sums itself (a second
+  // sweep inside the kernel), one partial array per workgroup of a KV head.
+  const bool evicts = L.count + n_tokens > cfg.budget;
+  const int own_partials = (cfg.n_q_heads / cfg.n_kv_heads) * aa.n_row_tiles;
+  const bool fused = evicts && mode == kScoreOwn && own_partials <= lay.max_partials && c->fused_scores;
+  if (fused) {
+    aa.partial = reinterpret_cast<float*>(set + lay.partial_off);
+    aa.n_partials = own_partials;
+    aa.cand_stride = lay.cand_stride;
+  }
+  int rc = launch(c, KVP_K_ATTENTION, 1, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
   if (rc) return rc;
-
-  // the scores decide an eviction; a block that fits into the cache as it is needs none
-  if (L.count + n_tokens > cfg.budget) {
+  aa.partial = nullptr;
+  if (fused) {
+    L.n_partials = own_partials;
+  } else if (evicts) {
     if (proxy) {
       // row statistics of the proxy queries over all candidates (nothing hidden, no output);
       // they replace the block's own in the scratch set
@@ -394,10 +457,10 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
         ra.n_q_heads = cfg.n_q_heads; ra.n_kv_heads = cfg.n_kv_heads;
         ra.budget = cfg.budget; ra.lse_stride = cfg.chunk_max;
         ra.scale_log2 = aa.scale_log2;
-        rc = launch(c, KVP_K_ROWSTAT, s, [&] { return launch_rowstat(ra, cfg.head_dim, s); });
+        rc = launch(c, KVP_K_ROWSTAT, 1, s, [&] { return launch_rowstat(ra, cfg.head_dim, s); });
       } else {
         plan_attention(aa, cfg.head_dim, c->attn_shape);
-        rc = launch(c, KVP_K_ATTENTION, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
+        rc = launch(c, KVP_K_ATTENTION, 1, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
       }
       if (rc) return rc;
     }
@@ -408,7 +471,7 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
       ka.sums = ka.scores + (size_t)cfg.n_kv_heads * lay.cand_stride;
       ka.c = L.count; ka.n_keys = n_tokens; ka.n_kv_heads = cfg.n_kv_heads;
       ka.budget = cfg.budget; ka.cand_stride = lay.cand_stride;
-      rc = launch(c, KVP_K_KEYDIFF, s, [&] { return launch_keydiff(ka, cfg.head_dim, s); });
+      rc = launch(c, KVP_K_KEYDIFF, 1, s, [&] { return launch_keydiff(ka, cfg.head_dim, s); });
       if (rc) return rc;
       L.n_partials = 1;
     } else {
@@ -421,7 +484,7 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
       cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
       cs.scale_log2 = aa.scale_log2;
       plan_colsum(cs, cfg.head_dim);
-      rc = launch(c, KVP_K_COLSUM, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
+      rc = launch(c, KVP_K_COLSUM, 1, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
       if (rc) return rc;
       L.n_partials = cs.n_partials;
     }
@@ -456,18 +519,7 @@ int kvp_prefill_chunk_keydiff(kvp_cache* c, int32_t layer, int32_t token_begin, 
 
 int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void* stream) {
   if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
-  Layer& L = c->layers[layer];
-  if (L.state != PENDING) return KVP_ESTATE;
-  const int before = L.count;
-  int rc = run_compact(c, layer, scores_override, static_cast<hipStream_t>(stream));
-  if (rc) {
-    L.count = before;
-    return rc;
-  }
-  L.state = READY;
-  L.next_token = L.t0 + L.n;
-  c->set_owner[layer % c->lay.n_sets] = -1;
-  return KVP_OK;
+  return compact_layers(c, layer, 1, scores_override, static_cast<hipStream_t>(stream));
 }
 
 int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const void* const* q,
@@ -485,7 +537,9 @@ int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const
   // event.  The streams so exchange two events per group instead of two per layer (a record
   // costs the main stream about 4 us, a wait about 6 us), and while the side stream compacts
   // one group the main stream has the other half of the sets for the next.
-  const int group = two ? std::max(1, n_sets / 2) : 1;
+  // On one stream a group may take every scratch set: its compactions then go out as one launch
+  // of each kernel for the whole group.
+  const int group = std::min(kMaxGroupLayers, two ? std::max(1, n_sets / 2) : n_sets);
   const size_t ring = (size_t)n_sets + 2;        // more than the groups any set can still refer to
   if (two && c->attended.empty()) {
     for (std::vector<hipEvent_t>* list : {&c->attended, &c->compacted})
@@ -524,8 +578,8 @@ int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const
       if (hipEventRecord(c->attended[slot], main) != hipSuccess) return KVP_EDEVICE;
       if (hipStreamWaitEvent(side, c->attended[slot], 0) != hipSuccess) return KVP_EDEVICE;
     }
-    for (int layer = first; layer < last; ++layer) {
-      const int rc2 = kvp_compact(c, layer, nullptr, two ? side_stream : stream);
+    if (last > first) {
+      const int rc2 = compact_layers(c, first, last - first, nullptr, two ? side : main);
       if (rc2) return rc2;
     }
     if (two && last > first) {
@@ -588,7 +642,7 @@ int kvp_decode_step(kvp_cache* c, int32_t layer, const void* q, const void* k_ta
   da.n_splits = decode_splits((long long)L.count + n_tail, cfg.head_dim, have, cfg.n_q_heads);
   if (da.n_splits < 1) return KVP_ENOMEM;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  return launch(c, KVP_K_DECODE, s, [&] { return launch_decode(da, cfg.head_dim, s); });
+  return launch(c, KVP_K_DECODE, 1, s, [&] { return launch_decode(da, cfg.head_dim, s); });
 }
 
 int kvp_decode_step_static(kvp_cache* c, int32_t layer, const void* q, const void* k_tail, const void* v_tail,
@@ -621,7 +675,7 @@ int kvp_decode_step_static(kvp_cache* c, int32_t layer, const void* q, const voi
   da.scale_log2 = c->scale * 1.4426950408889634f;
   da.n_splits = splits;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  return launch(c, KVP_K_DECODE, s, [&] { return launch_decode(da, cfg.head_dim, s); });
+  return launch(c, KVP_K_DECODE, 1, s, [&] { return launch_decode(da, cfg.head_dim, s); });
 }
 
 int kvp_set_state(kvp_cache* c, int32_t layer, int32_t count, int32_t next_token) {
@@ -644,6 +698,12 @@ int kvp_set_attention_shape(kvp_cache* c, int32_t shape) {
   return KVP_OK;
 }
 
+int kvp_set_score_sweep(kvp_cache* c, int32_t fused) {
+  if (!c || (fused != 0 && fused != 1)) return KVP_EINVAL;
+  c->fused_scores = fused != 0;
+  return KVP_OK;
+}
+
 int kvp_debug_last(kvp_cache* c, int32_t layer, const float** scores, const uint8_t** keep,
                    const int32_t** dst, int32_t* n_cand, int32_t* stride) {
   if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
@@ -658,6 +718,12 @@ int kvp_debug_last(kvp_cache* c, int32_t layer, const float** scores, const uint
   return KVP_OK;
 }
 
+int kvp_debug_totals(kvp_cache* c, const uint64_t** totals) {
+  if (!c || !totals) return KVP_EINVAL;
+  *totals = c->dry ? nullptr : reinterpret_cast<const uint64_t*>(c->totals());
+  return KVP_OK;
+}
+
 int kvp_profile_enable(kvp_cache* c, int32_t on) {
   if (!c) return KVP_EINVAL;
   c->profiling = on != 0 && !c->dry;
@@ -666,7 +732,7 @@ int kvp_profile_enable(kvp_cache* c, int32_t on) {
 
 int kvp_profile_read(kvp_cache* c, kvp_kernel_stat* stats) {
   if (!c || !stats) return KVP_EINVAL;
-  for (int i = 0; i < KVP_K_COUNT; ++i) stats[i] = kvp_kernel_stat{0, 0.0};
+  for (int i = 0; i < KVP_K_COUNT; ++i) stats[i] = kvp_kernel_stat{0, 0, 0.0};
   int rc = KVP_OK;
   for (ProfEvent& pe : c->events) {
     float ms = 0.f;
@@ -674,6 +740,7 @@ int kvp_profile_read(kvp_cache* c, kvp_kernel_stat* stats) {
       rc = KVP_EDEVICE;
     } else {
       stats[pe.kind].launches += 1;
+      stats[pe.kind].layers += pe.layers;
       stats[pe.kind].total_ms += ms;
     }
     c->pool.push_back(pe.start);

@@ -13,6 +13,26 @@ typedef unsigned short u16;  // one bfloat16 bit pattern
 constexpr int kXcds = 8;            // MI355X: 8 accelerator dies, each with its own L2
 constexpr int kNeighbours = 6;      // 4 in the plane + 2 in time
 
+// Sizes that the kernels and the host-side planning (plan.cpp) must agree on.
+constexpr int kAttnRowsOfShape[3] = {128, 64, 128};   // query rows per workgroup of the three attention shapes
+constexpr int kColsumWaves = 4;                 // waves per workgroup of the column-sum kernel
+constexpr int kColsumTargetWorkgroups = 512;    // two per CU, all resident: the launch is a single round
+constexpr int kColsumMaxRowSplits = 16;
+constexpr int kSelectThreads = 1024;
+constexpr int kSelectCopies = 32;               // histogram replicas of the radix select
+constexpr int kRowstatBlockKeys = 512;          // keys per workgroup of the proxy row-statistics kernel
+constexpr int kKeydiffSliceKeys = 64;           // keys per workgroup of the key-sum kernel
+constexpr int kDecodeTile = 64;                 // keys per workgroup step of the decode kernel
+constexpr int kDecodeMaxSplits = 128;
+constexpr int kDecodeGroupLimit = 16;           // query heads per KV head the decode kernel is built for
+constexpr int kCompactThreads = 256;
+
+// bytes of the select kernel's region that is first the radix histogram and then the compaction lists
+constexpr size_t select_region_bytes(size_t cand_pad) {
+  const size_t hist = (size_t)256 * kSelectCopies * 4, lists = cand_pad * 5;
+  return (hist > lists ? hist : lists + 15) / 16 * 16;
+}
+
 // One block of one layer attending over cache U block (Eq. 1).
 struct AttnArgs {
   const u16* q;        // [n, Hq, D]
@@ -22,6 +42,9 @@ struct AttnArgs {
   const u16* k_cache;  // this layer: [Hkv, M, D]
   const u16* v_cache;
   float* lse2;         // [Hq, lse_stride]  log2-domain log-sum-exp of every row
+  float* partial;      // null, or [Hkv, n_partials, cand_stride]: the launch also leaves the column sums
+                       // of its softmax matrix (Eq. 4), one array per workgroup of a KV head
+  int n_partials, cand_stride;   // n_partials = query heads per KV head x n_row_tiles
   int n, c, n_q_heads, n_kv_heads, budget, lse_stride;
   int n_keys;          // block keys (k_new, v_new rows); the query rows are n
   int shift;           // row r sees block key j iff j <= r + shift (0: causal block; >= n_keys: all)
@@ -121,7 +144,22 @@ struct DstEntry {
   int src[kNeighbours];     // candidate positions of its sources
 };
 
+// A launch of the selection and compaction kernels covers a group of consecutive layers that hold
+// the same block (same c, n, t0).  The pointers in SelectArgs and CompactArgs are those of the
+// group's FIRST layer; layer i of the group is reached through the strides below.
+constexpr int kMaxGroupLayers = 16;
+struct LayerGroup {
+  int n_layers;
+  int first_set, n_sets;        // layer i uses scratch set (first_set + i) % n_sets
+  long long set_stride;         // bytes between scratch sets
+  long long kv_stride;          // bf16 elements between the K (or V) caches of consecutive layers
+  long long meta_stride;        // elements between their token_idx (or weight) arrays
+  const u16* k_new[kMaxGroupLayers];   // the block's keys and values of every layer of the group
+  const u16* v_new[kMaxGroupLayers];
+};
+
 struct SelectArgs {
+  LayerGroup g;
   const float* partial;         // [Hkv, n_partials, cand_stride] or null when override is set
   const float* score_override;  // [Hkv, n_cand] or null
   float* scores;                // [Hkv, cand_stride]   scores actually used
@@ -132,6 +170,7 @@ struct SelectArgs {
   MoveEntry* moves;             // [Hkv, chunk_max]
   DstEntry* dsts;               // [Hkv, chunk_max]
   const Seg* segs;
+  unsigned long long* totals;   // [KVP_T_COUNT] running totals of the cache (kvp_debug_totals)
   int n_segs;
   int c, n, t0, budget, cand_stride, chunk_max, n_partials, merge;
   int items;                    // candidates per thread
@@ -139,12 +178,11 @@ struct SelectArgs {
 };
 
 struct CompactArgs {
-  u16* k_cache;            // this layer
+  LayerGroup g;
+  u16* k_cache;            // the group's first layer
   u16* v_cache;
   int32_t* token_idx;
   float* weight;
-  const u16* k_new;
-  const u16* v_new;
   const HeadCounts* counts;
   const MoveEntry* moves;
   const DstEntry* dsts;
@@ -159,15 +197,17 @@ struct CompactArgs {
 // launchers (each returns the hipError_t of the launch)
 hipError_t launch_attention(const AttnArgs& a, int head_dim, hipStream_t s);
 hipError_t launch_colsum(const ColsumArgs& a, int head_dim, hipStream_t s);
-hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s);
+hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s);   // grid: heads x a.g.n_layers
 hipError_t launch_merge(const CompactArgs& a, hipStream_t s);
 hipError_t launch_move(const CompactArgs& a, hipStream_t s);
 hipError_t launch_init(int32_t* token_idx, float* weight, size_t n_slots, const Seg* host_segs,
-                       int n_segs, Seg* dev_segs, hipStream_t s);
-int rows_per_compact_block();
+                       int n_segs, Seg* dev_segs, unsigned long long* totals, hipStream_t s);
+int rows_per_compact_block(int head_dim);
 
 // host-side planning shared by launchers and the state machine
 void plan_attention(AttnArgs& a, int head_dim, int forced_shape);   // forced_shape < 0: chosen from the launch size
+int attention_max_partials(int group, int chunk_max);   // most partial score arrays per KV head a launch can leave
+constexpr int kMaxFusedPartials = 64;                   // beyond that the separate column-sum kernel scores
 hipError_t prepare_attention();   // function attributes on the current device; once per cache creation
 hipError_t prepare_select();
 void plan_colsum(ColsumArgs& a, int head_dim);

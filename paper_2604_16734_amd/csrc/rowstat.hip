@@ -25,7 +25,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kSub = 4;                        // 32-key subtiles per wave
 constexpr int kWaveKeys = 32 * kSub;
-constexpr int kBlockKeys = 4 * kWaveKeys;      // 512
+constexpr int kBlockKeys = 4 * kWaveKeys;
+static_assert(kBlockKeys == kRowstatBlockKeys, "the host plans with this block size");
 
 __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
 
@@ -111,8 +112,6 @@ __global__ void rowstat_fold_kernel(const RowstatArgs a) {
 }
 
 }  // namespace
-
-int rowstat_key_blocks(int n_cand) { return (n_cand + kBlockKeys - 1) / kBlockKeys; }
 
 hipError_t launch_rowstat(RowstatArgs a, int head_dim, hipStream_t s) {
   a.n_kv_blocks = rowstat_key_blocks(a.c + a.n_keys);

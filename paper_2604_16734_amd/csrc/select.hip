@@ -24,10 +24,10 @@
 namespace kvp {
 namespace {
 
-constexpr int kThreads = 1024;
+constexpr int kThreads = kSelectThreads;
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxItemsAny = KVP_MAX_CANDIDATES / kThreads;   // 8
-constexpr int kCopies = 32;                                // histogram replicas
+constexpr int kCopies = kSelectCopies;                     // histogram replicas
 constexpr unsigned kNone16 = 0xFFFFu;
 
 __device__ __forceinline__ unsigned order_bits(float x) {
@@ -44,12 +44,6 @@ __device__ __forceinline__ unsigned hash_tok(int tok, unsigned mask) {
   unsigned x = (unsigned)tok * 0x9E3779B1u;
   x ^= x >> 15;
   return x & mask;
-}
-
-// bytes of the region that is first the radix histogram and then the compaction lists
-__host__ __device__ inline size_t select_region_bytes(size_t cand_pad) {
-  const size_t hist = (size_t)256 * kCopies * 4, lists = cand_pad * 5;
-  return (hist > lists ? hist : lists + 15) / 16 * 16;
 }
 
 struct Lds {
@@ -135,9 +129,30 @@ __device__ __forceinline__ bool neighbours(const SegL* segs, int n_segs, int tok
 
 // kMaxItems: candidates a thread can own (4 covers up to 4096 candidates and halves the registers
 // of the batched loads; 8 covers the limit)
+// the same pointer in scratch set (first_set + li) % n_sets instead of set first_set
+template <class T>
+__device__ __forceinline__ T* in_set_of(T* p, const LayerGroup& g, int li) {
+  if (p == nullptr) return p;
+  const long long sets = (long long)((g.first_set + li) % g.n_sets) - g.first_set;
+  return reinterpret_cast<T*>(reinterpret_cast<uintptr_t>(p) + (uintptr_t)(sets * g.set_stride));
+}
+
 template <int kMaxItems>
 __global__ void __launch_bounds__(kThreads)
-select_kernel(const SelectArgs a) {
+select_kernel(const SelectArgs a_first) {
+  // grid (KV heads, layers of the group): this workgroup's layer
+  SelectArgs a = a_first;
+  {
+    const int li = blockIdx.y;
+    a.partial = in_set_of(a.partial, a.g, li);
+    a.scores = in_set_of(a.scores, a.g, li);
+    a.keep = in_set_of(a.keep, a.g, li);
+    a.dst = in_set_of(a.dst, a.g, li);
+    a.counts = in_set_of(a.counts, a.g, li);
+    a.moves = in_set_of(a.moves, a.g, li);
+    a.dsts = in_set_of(a.dsts, a.g, li);
+    a.token_idx += (long long)li * a.g.meta_stride;
+  }
   extern __shared__ __align__(16) unsigned char lds_raw[];
   __shared__ unsigned long long s_threshold;
   __shared__ unsigned s_digit, s_want, s_bin_count;
@@ -406,7 +421,11 @@ select_kernel(const SelectArgs a) {
       moves[rank_new[i]] = e;
     }
   }
-  if (tid == 0) a.counts[hk].n_moves = (int)total_new;
+  if (tid == 0) {
+    a.counts[hk].n_moves = (int)total_new;
+    atomicAdd(&a.totals[KVP_T_EVICTING_HEADS], 1ull);
+    atomicAdd(&a.totals[KVP_T_MOVED_ROWS], (unsigned long long)total_new);
+  }
 
   if (!a.merge) {
     if (tid == 0) a.counts[hk].n_dst = 0;
@@ -503,27 +522,30 @@ select_kernel(const SelectArgs a) {
   }
   __syncthreads();
   // every source writes itself into its destination's entry
+  unsigned n_src_mine = 0;
   for (unsigned e = tid; e < total_ev; e += kThreads) {
     const unsigned d = l.free_dst[e];
     if (d == kNone16) continue;
     const unsigned old = atomicAdd(&fill[d >> 2], 1u << (8 * (d & 3)));
     const unsigned k = (old >> (8 * (d & 3))) & 0xFFu;
     dsts[l.sc[d]].src[k] = l.evicted[e];
+    ++n_src_mine;
   }
   if (tid == 0) a.counts[hk].n_dst = (int)n_dst;
+  // running totals for the benchmark's byte counts (integer atomics: the order does not matter)
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) n_src_mine += __shfl_xor(n_src_mine, off, 64);
+  if (lane == 0 && n_src_mine) atomicAdd(&a.totals[KVP_T_MERGE_SOURCES], (unsigned long long)n_src_mine);
+  if (tid == 0) atomicAdd(&a.totals[KVP_T_MERGE_DESTINATIONS], (unsigned long long)n_dst);
 }
 
 }  // namespace
 
-size_t select_lds_bytes(int /*n_cand*/, int items, int table_size) {
-  const size_t cand_pad = (size_t)items * kThreads;
-  return cand_pad * (4 + 4 + 1) + select_region_bytes(cand_pad) + (size_t)table_size * 2;
-}
-
 hipError_t launch_select(const SelectArgs& a, int n_kv_heads, hipStream_t s) {
   const size_t lds = select_lds_bytes(a.c + a.n, a.items, a.table_size);
-  if (a.items <= 4) hipLaunchKernelGGL(select_kernel<4>, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
-  else hipLaunchKernelGGL(select_kernel<kMaxItemsAny>, dim3(n_kv_heads), dim3(kThreads), lds, s, a);
+  const dim3 grid(n_kv_heads, a.g.n_layers);
+  if (a.items <= 4) hipLaunchKernelGGL(select_kernel<4>, grid, dim3(kThreads), lds, s, a);
+  else hipLaunchKernelGGL(select_kernel<kMaxItemsAny>, grid, dim3(kThreads), lds, s, a);
   return hipGetLastError();
 }
 
