@@ -137,7 +137,7 @@ def attainable_peaks(device):
                    "kvp_probe_copy: 256 MiB, read + written bytes, best of four grid sizes; medians of 5" % cus}
 
 
-def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=8, variants=True):
+def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=16, variants=True):
     import torch
     import paper_2604_16734_amd as K
     from kvp_workload import chunk_ranges
@@ -359,7 +359,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
                     help="2: kvp_compact of a layer runs on a second stream beside the next layers' kvp_prefill_chunk")
-    ap.add_argument("--scratch-sets", type=int, default=8,
+    ap.add_argument("--scratch-sets", type=int, default=16,
                     help="scratch sets of the cache with two streams: the layers go in groups of (sets / 2), "
                          "two events between the streams per group")
     ap.add_argument("--n-obs", type=int, default=64,

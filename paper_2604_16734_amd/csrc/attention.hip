@@ -780,45 +780,59 @@ attention_kernel(const AttnArgs a) {
     float sl2_copy[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) asm volatile("v_mov_b32 %0, %1" : "=v"(sl2_copy[i]) : "s"(sl2));
+    // A slot is one key block against kR consecutive row tiles (64 rows when a workgroup has four
+    // row tiles: its first two tiles are neighbours, and so are its last two): kR independent
+    // chains of matrix instructions, and the costs a slot pays once -- the wait for its first
+    // fragments, picking its variant, the distance to the first read of its result -- are shared
+    // by twice the work.
+    constexpr int kR = kRowTiles == 4 ? 2 : 1;
+    constexpr int kSlots = kRowTiles / kR;
+    static_assert(kSlots % 2 == 0, "the two accumulator sets alternate over the slots");
     // The slot before the current one: its logits wait in the other accumulator set.
     bool p_vis = false, p_plain = false;
     int p_kb0 = 0, p_row0 = 0, p_tile = 0;
 
-    // One slot: the MFMAs of (key block, row tile) into s_new among the exponentials of the slot
+    // One slot: the MFMAs of (key block, row tiles) into s_new among the exponentials of the slot
     // before it from s_exp, laid out MFMA by MFMA as in the first sweep.  Returns this lane's sum
-    // of the exponentiated slot over its 16 rows.
-    auto stage = [&](const f32x16& s_exp, f32x16& s_new, const u16* qt, const bf16x8 (&kf)[kNK], auto do_mfma,
-                     auto do_exp, auto mask) __attribute__((always_inline)) -> float {
+    // of the exponentiated slot over its 16 kR rows.
+    auto stage = [&](const f32x16 (&s_exp)[kR], f32x16 (&s_new)[kR], const u16* qt, const bf16x8 (&kf)[kNK],
+                     auto do_mfma, auto do_exp, auto mask) __attribute__((always_inline)) -> float {
       constexpr bool kMfma = decltype(do_mfma)::value, kExp = decltype(do_exp)::value, kMask = decltype(mask)::value;
-      constexpr int kPer = kMfma ? 16 / kNK : 16;
+      constexpr int kElems = 16 * kR;
+      constexpr int kPer = kMfma ? 16 / kNK : kElems;      // elements per matrix instruction
       constexpr int kAhead = kNK < 4 ? kNK : 4;
-      bf16x8 qfr[kNK];
-      float ls[16];
+      bf16x8 qfr[kR][kNK];
+      float ls[kR][16];
       float sum[2] = {0.f, 0.f};
-      int first = 0;
-      unsigned span = 0;
+      int first[kR];
+      unsigned span[kR];
       if constexpr (kExp) {
         // statistics of the previous slot's rows: register r is row 8 (r / 4) + 4 g + r % 4 of its tile
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(&lse_lds[p_tile * 32 + 8 * j + 4 * g]);
-          ls[4 * j] = v[0]; ls[4 * j + 1] = v[1]; ls[4 * j + 2] = v[2]; ls[4 * j + 3] = v[3];
-        }
+        for (int t = 0; t < kR; ++t)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(&lse_lds[(p_tile + t) * 32 + 8 * j + 4 * g]);
+            ls[t][4 * j] = v[0]; ls[t][4 * j + 1] = v[1]; ls[t][4 * j + 2] = v[2]; ls[t][4 * j + 3] = v[3];
+          }
         if constexpr (kMask) {
-          // key p_kb0 + l32 counts for the row at offset off = 8 (r / 4) + r % 4 from p_row0 + 4 g
-          // iff first <= off < rows left in the block
-          const int row0 = p_row0 + 4 * g;
-          first = p_kb0 + l32 - c - shift - row0;                 // negative for a cached key
-          span = (unsigned)max(n - row0 - first, 0);
+          // key p_kb0 + l32 counts for the row at offset off = 8 (r / 4) + r % 4 from the tile's row
+          // 4 g iff first <= off < rows left in the block
+#pragma unroll
+          for (int t = 0; t < kR; ++t) {
+            const int row0 = p_row0 + 32 * t + 4 * g;
+            first[t] = p_kb0 + l32 - c - shift - row0;            // negative for a cached key
+            span[t] = (unsigned)max(n - row0 - first[t], 0);
+          }
         }
       }
       const float sl2_here = sl2_copy[(kMfma ? 0 : 2) + (kMask ? 1 : 0)];
       int ei = 0;
       float arg = 0.f, pe1 = 0.f;
-      if constexpr (kExp) arg = __builtin_fmaf(s_exp[0], sl2_here, -ls[0]);
+      if constexpr (kExp) arg = __builtin_fmaf(s_exp[0][0], sl2_here, -ls[0][0]);
       auto finish_element = [&](int e) __attribute__((always_inline)) {      // element e is in pe1
         float p = pe1;
-        if constexpr (kMask) p = (unsigned)(8 * (e >> 2) + (e & 3) - first) < span ? p : 0.f;
+        if constexpr (kMask) p = (unsigned)(8 * ((e % 16) >> 2) + (e & 3) - first[e / 16]) < span[e / 16] ? p : 0.f;
         sum[e & 1] += p;
         asm volatile("" : "+v"(sum[e & 1]));
       };
@@ -827,7 +841,8 @@ attention_kernel(const AttnArgs a) {
 #pragma unroll
           for (int k = 0; k < kPer; ++k, ++ei) {
             const float pe = __builtin_amdgcn_exp2f(arg);
-            if (ei + 1 < 16) arg = __builtin_fmaf(s_exp[ei + 1], sl2_here, -ls[ei + 1]);
+            if (ei + 1 < kElems)
+              arg = __builtin_fmaf(s_exp[(ei + 1) / 16][(ei + 1) % 16], sl2_here, -ls[(ei + 1) / 16][(ei + 1) % 16]);
             if (ei >= 1) finish_element(ei - 1);
             pe1 = pe;
           }
@@ -835,19 +850,24 @@ attention_kernel(const AttnArgs a) {
       };
       if constexpr (kMfma) {
 #pragma unroll
-        for (int st = 0; st < kAhead; ++st) qfr[st] = lds_read_b128(qt + k_off[st]);
+        for (int st = 0; st < kAhead; ++st)
+#pragma unroll
+          for (int t = 0; t < kR; ++t) qfr[t][st] = lds_read_b128(qt + t * 32 * D + k_off[st]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int st = 0; st < kNK; ++st) {
-          if (st + kAhead < kNK) qfr[st + kAhead] = lds_read_b128(qt + k_off[st + kAhead]);
-          s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[st], kf[st], st == 0 ? zero : s_new, 0, 0, 0);
-          exp_some();
-          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int t = 0; t < kR; ++t) {
+            if (st + kAhead < kNK) qfr[t][st + kAhead] = lds_read_b128(qt + t * 32 * D + k_off[st + kAhead]);
+            s_new[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[t][st], kf[st], st == 0 ? zero : s_new[t], 0, 0, 0);
+            exp_some();
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
       } else {
         exp_some();
       }
-      if constexpr (kExp) finish_element(15);
+      if constexpr (kExp) finish_element(kElems - 1);
       if constexpr (kMfma) {
         // A vector instruction may read the result of a 32x32x16 matrix instruction only twelve wait
         // states after it was issued.  The next reader of s_new sits in another basic block (the next
@@ -863,7 +883,7 @@ attention_kernel(const AttnArgs a) {
     typedef std::true_type Yes;
     typedef std::false_type No;
     // the slot as it stands: is the current pair visible at all, was the previous one, did it need the mask
-    auto slot = [&](const f32x16& s_exp, f32x16& s_new, const u16* qt, const bf16x8 (&kf)[kNK], bool vis)
+    auto slot = [&](const f32x16 (&s_exp)[kR], f32x16 (&s_new)[kR], const u16* qt, const bf16x8 (&kf)[kNK], bool vis)
         __attribute__((always_inline)) -> float {
       if (vis) {
         if (!p_vis) return stage(s_exp, s_new, qt, kf, Yes{}, No{}, No{});
@@ -878,7 +898,9 @@ attention_kernel(const AttnArgs a) {
       if (g == 0 && kv < n_cand) part[kv] = tot;
     };
 
-    f32x16 sa = zero, sb = zero;
+    f32x16 sa[kR], sb[kR];
+#pragma unroll
+    for (int t = 0; t < kR; ++t) { sa[t] = zero; sb[t] = zero; }
     float carry = 0.f;             // sums of the block before the current one, its last slot still to come
     int carry_kb = -1;
     // all row tiles against one key block; the next block of this wave is fetched meanwhile
@@ -886,27 +908,29 @@ attention_kernel(const AttnArgs a) {
       const int kb0 = kbi * 32;
       float acc = 0.f;
 #pragma unroll
-      for (int i = 0; i < kRowTiles; ++i) {
-        const int row0 = first_row_of(i / QT) + 32 * (i % QT);
-        // some row of the tile sees some key of the block; every row sees every key and all are real
-        const bool vis = row0 < n && (kb0 < c || kb0 - c <= row0 + 31 + shift);
-        const bool plain = kb0 + 31 < n_cand && (kb0 + 31 < c || kb0 + 31 - c <= row0 + shift) && row0 + 32 <= n;
-        const float got = (i & 1) ? slot(sa, sb, q_lds + i * 32 * D, kf, vis) : slot(sb, sa, q_lds + i * 32 * D, kf, vis);
+      for (int i = 0; i < kSlots; ++i) {
+        // the slot's rows: row0 .. row0 + 32 kR - 1 (row tiles kR i .. kR i + kR - 1 are neighbours)
+        const int tile = kR * i;
+        const int row0 = first_row_of(tile / QT) + 32 * (tile % QT);
+        // some row of the slot sees some key of the block; every row sees every key and all are real
+        const bool vis = row0 < n && (kb0 < c || kb0 - c <= row0 + 32 * kR - 1 + shift);
+        const bool plain = kb0 + 31 < n_cand && (kb0 + 31 < c || kb0 + 31 - c <= row0 + shift) && row0 + 32 * kR <= n;
+        const float got = (i & 1) ? slot(sa, sb, q_lds + tile * 32 * D, kf, vis) : slot(sb, sa, q_lds + tile * 32 * D, kf, vis);
         if (i == 0) {
           if (carry_kb >= 0) store_block(carry_kb, carry + got);   // the last slot of the block before
         } else {
           acc += got;
         }
-        p_vis = vis; p_plain = plain; p_kb0 = kb0; p_row0 = row0; p_tile = i;
+        p_vis = vis; p_plain = plain; p_kb0 = kb0; p_row0 = row0; p_tile = tile;
       }
       carry = acc;
       carry_kb = kbi;
     };
     // This wave's key blocks are wave, wave + kWaves, ...; two register sets take turns, the block
-    // after the current one is on its way while the current one is worked on.  The fetches are
-    // unconditional (past the wave's last block they read it again): the compiler counts the loads
-    // in flight to place its waits, and a fetch that may or may not have been issued would make it
-    // wait for the newest one.
+    // after the current one is on its way while the current one is worked on (a third set, two
+    // blocks ahead, was tried: it spills and is slower).  The fetches are unconditional (past the
+    // wave's last block they read it again): the compiler counts the loads in flight to place its
+    // waits, and a fetch that may or may not have been issued would make it wait for the newest one.
     bf16x8 kfa[kNK], kfb[kNK];
     const int last_kb = max(n_kb - 1, 0);
     load_keys(kfa, min(wave_s, last_kb));

@@ -67,7 +67,7 @@ Layout make_layout(const kvp_config& c) {
   // group x row tiles), as long as that stays modest
   L.max_partials = colsum_max_partials(c.n_q_heads / c.n_kv_heads, c.chunk_max);
   {
-    const int fused = attention_max_partials(c.n_q_heads / c.n_kv_heads, c.chunk_max);
+    const int fused = attention_max_partials(c.n_q_heads / c.n_kv_heads, c.n_q_heads, c.chunk_max);
     if (fused <= kMaxFusedPartials && fused > L.max_partials) L.max_partials = fused;
   }
   size_t s = 0;

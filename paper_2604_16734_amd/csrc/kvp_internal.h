@@ -206,7 +206,7 @@ int rows_per_compact_block(int head_dim);
 
 // host-side planning shared by launchers and the state machine
 void plan_attention(AttnArgs& a, int head_dim, int forced_shape);   // forced_shape < 0: chosen from the launch size
-int attention_max_partials(int group, int chunk_max);   // most partial score arrays per KV head a launch can leave
+int attention_max_partials(int group, int n_q_heads, int chunk_max);   // most partial score arrays per KV head a launch leaves
 constexpr int kMaxFusedPartials = 64;                   // beyond that the separate column-sum kernel scores
 hipError_t prepare_attention();   // function attributes on the current device; once per cache creation
 hipError_t prepare_select();

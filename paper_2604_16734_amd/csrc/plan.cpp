@@ -6,14 +6,25 @@
 namespace kvp {
 
 // ---- attention
-// 64-row workgroups are the smallest: the most row tiles, the most partial arrays
-int attention_max_partials(int group, int chunk_max) { return group * ((chunk_max + 63) / 64); }
+// eight waves x 32 rows (two waves per SIMD) when 128-row workgroups fill the chip, otherwise four
+// waves x 32 rows over 64-row workgroups
+static int shape_for(int n, int n_q_heads) { return ((n + 127) / 128) * n_q_heads >= 192 ? 2 : 1; }
+
+// The most partial score arrays per KV head (query heads of the group x row tiles) that a block of
+// up to chunk_max rows leaves when the library picks the shape itself.  A forced shape may need
+// more; such a launch then scores with the separate kernel.
+int attention_max_partials(int group, int n_q_heads, int chunk_max) {
+  int most = 0;
+  for (int n = 1; n <= chunk_max; ++n) {
+    const int rows = kAttnRowsOfShape[shape_for(n, n_q_heads)];
+    const int tiles = (n + rows - 1) / rows;
+    most = tiles > most ? tiles : most;
+  }
+  return group * most;
+}
 
 void plan_attention(AttnArgs& a, int /*head_dim*/, int forced_shape) {
-  auto wgs = [&](int rows) { return ((a.n + rows - 1) / rows) * a.n_q_heads; };
-  // eight waves x 32 rows (two waves per SIMD) when 128-row workgroups fill the chip,
-  // otherwise four waves x 32 rows over 64-row workgroups
-  a.variant = wgs(128) >= 192 ? 2 : 1;
+  a.variant = shape_for(a.n, a.n_q_heads);
   if (forced_shape >= 0 && forced_shape <= 2) a.variant = forced_shape;      // kvp_set_attention_shape
   const int rows = kAttnRowsOfShape[a.variant];
   a.n_row_tiles = (a.n + rows - 1) / rows;
