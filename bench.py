@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, vendor figure
 # HBM bytes per attention launch (fetch + write) at the long_video steady state, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (launch-weighted mean,
 # counters scaled by what they read for a plain 256 MiB copy); None for a workload not measured
-ATTENTION_TRAFFIC_BYTES = {"long_video": 28214600}
+ATTENTION_TRAFFIC_BYTES = {"long_video": 52320539}
 
 
 def attention_flops(wl, t0_n_pairs):
@@ -145,9 +145,9 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
     data = generate(wl, device, threads)
     ranges = chunk_ranges(wl.n_tokens, wl.chunk)
     two = streams == 2 and wl.n_layers >= 4
-    scratch_sets = max(2, min(scratch_sets, wl.n_layers))
+    scratch_sets = max(2 if two else 1, min(scratch_sets, wl.n_layers))
     cache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
-                    wl.segments, merge=True, scratch_sets=scratch_sets if two else 1, device=device)
+                    wl.segments, merge=True, scratch_sets=scratch_sets, device=device)
     driver = K.Prefill(cache, wl.n_layers, overlap=two)
     outs = [torch.empty((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=device)
             for _ in range(wl.n_layers)]
@@ -186,7 +186,7 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
     if variants and wl.budget > wl.chunk and wl.budget + wl.budget <= 8192 and wl.n_tokens > wl.budget:
         # hybrid execution (Sec. 4.3): the first `budget` tokens in one causal pass, then blocks
         bcache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.budget,
-                         wl.segments, merge=True, scratch_sets=scratch_sets if two else 1, device=device)
+                         wl.segments, merge=True, scratch_sets=scratch_sets, device=device)
         bdriver = K.Prefill(bcache, wl.n_layers, overlap=two)
         branges = [(0, wl.budget)] + [(wl.budget + t0, n) for t0, n in chunk_ranges(wl.n_tokens - wl.budget, wl.chunk)]
         bouts = [torch.empty((wl.budget, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=device)
@@ -360,8 +360,9 @@ def main():
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
                     help="2: kvp_compact of a layer runs on a second stream beside the next layers' kvp_prefill_chunk")
     ap.add_argument("--scratch-sets", type=int, default=16,
-                    help="scratch sets of the cache with two streams: the layers go in groups of (sets / 2), "
-                         "two events between the streams per group")
+                    help="scratch sets of the cache: one select/merge/move launch covers a group of layers, "
+                         "sets / 2 of them with two streams (two events between the streams per group), "
+                         "min(sets, 16) with one")
     ap.add_argument("--n-obs", type=int, default=64,
                     help="also time the prefill scored with this many proxy queries (0: skip)")
     ap.add_argument("--variants", type=int, default=1,
@@ -424,6 +425,9 @@ def main():
             e["note"] = note
         return e
 
+    executed = main_res["attention_flops_per_launch"]
+    if "colsum" not in kern:
+        executed += main_res["colsum_flops_per_step"] / att["launches_per_step"]
     rooflines = [entry("attention", "mfma", achieved, "TFLOP/s", "flops_per_launch", main_res["attention_flops_per_launch"])]
     if "colsum" in kern:
         f = main_res["colsum_flops_per_step"]
@@ -482,6 +486,11 @@ def main():
             "attention_plus_scoring_tflops": round(main_res["attention_plus_scoring_tflops"], 2),
             "attention_plus_scoring_frac": round(main_res["attention_plus_scoring_tflops"] / PEAK_BF16_TFLOPS, 4),
             "frac_of_attainable": round(achieved / peaks["mfma_bf16_tflops"], 4) if peaks else None,
+            # context, not the roofline figure: the launch recomputes QK^T for the scores (Eq. 4 needs
+            # every row's final normaliser), so its matrix pipe executes these flops, not flops_per_launch
+            "mfma_flops_executed_per_launch": executed,
+            "executed_tflops": round(executed / (att["avg_us"] * 1e-6) / 1e12, 2),
+            "executed_frac": round(executed / (att["avg_us"] * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
         },
         "rooflines": rooflines,
         "select_merge_move": {
