@@ -159,6 +159,21 @@ int kvp_prefill_chunk_keydiff(kvp_cache* cache, int32_t layer, int32_t token_beg
  * first, then block tokens) used instead of the computed scores. */
 int kvp_compact(kvp_cache* cache, int32_t layer, const float* scores_override, void* stream);
 
+/* kvp_compact (Alg. 1 lines 7-11) for the consecutive layers first_layer ..
+ * first_layer + n_layers - 1, every one of them PENDING.  For a model that runs
+ * its layers one after the other: kvp_prefill_chunk per layer as the block
+ * moves up the stack (the cache needs one scratch set per layer that is pending
+ * at a time), then this call once for all of them.  Layers that are in the same
+ * state (same entry count, same block, scored the same way -- the case in a
+ * prefill) are taken up to 16 at a time by ONE select, ONE merge and ONE move
+ * launch, which fills the GPU where a single layer's KV heads cannot; others are
+ * taken one by one.  The result is that of n_layers kvp_compact calls, bit for
+ * bit.  Every layer's k and v must still be valid.
+ *   KVP_EINVAL  bad range;  KVP_ESTATE  a layer of the range is not PENDING
+ * (both before anything is enqueued).  KVP_EDEVICE: a launch failed; the layers
+ * of the groups launched before it are READY, the rest still PENDING. */
+int kvp_compact_layers(kvp_cache* cache, int32_t first_layer, int32_t n_layers, void* stream);
+
 /* One block of the prefix through every layer (the body of the loop of Alg. 1,
  * for all layers): for layer 0 .. n_layers-1, kvp_prefill_chunk (or its proxy or
  * key-only scoring variant) followed by kvp_compact.

@@ -93,6 +93,8 @@ def lib():
         L.kvp_prefill_join.argtypes = [vp, vp, vp]
         L.kvp_compact.restype = ctypes.c_int
         L.kvp_compact.argtypes = [vp, i32, vp, vp]
+        L.kvp_compact_layers.restype = ctypes.c_int
+        L.kvp_compact_layers.argtypes = [vp, i32, i32, vp]
         L.kvp_decode_step.restype = ctypes.c_int
         L.kvp_decode_step.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp]
         L.kvp_decode_step_static.restype = ctypes.c_int
@@ -201,6 +203,10 @@ def kvp_prefill_join(handle, stream=0, side_stream=None):
 
 def kvp_compact(handle, layer, scores_override=None, stream=0):
     return lib().kvp_compact(handle, layer, scores_override, stream)
+
+
+def kvp_compact_layers(handle, first_layer, n_layers, stream=0):
+    return lib().kvp_compact_layers(handle, first_layer, n_layers, stream)
 
 
 def kvp_decode_ready(handle, layer):
@@ -401,6 +407,9 @@ class Cache:
         if scores_override is not None:
             ptr = self._ptr(scores_override, self.torch.float32)
         _check(kvp_compact(self.handle, layer, ptr, self._stream(stream)), "kvp_compact")
+
+    def compact_layers(self, first_layer, n_layers, stream=None):
+        _check(kvp_compact_layers(self.handle, first_layer, n_layers, self._stream(stream)), "kvp_compact_layers")
 
     def _view_tensor(self, ptr, shape, dtype):
         """A tensor aliasing part of the device buffer."""

@@ -522,6 +522,19 @@ int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void*
   return compact_layers(c, layer, 1, scores_override, static_cast<hipStream_t>(stream));
 }
 
+int kvp_compact_layers(kvp_cache* c, int32_t first_layer, int32_t n_layers, void* stream) {
+  if (!c || first_layer < 0 || n_layers < 1 || n_layers > c->cfg.n_layers || first_layer > c->cfg.n_layers - n_layers)
+    return KVP_EINVAL;
+  for (int i = 0; i < n_layers; ++i)
+    if (c->layers[first_layer + i].state != PENDING) return KVP_ESTATE;
+  for (int done = 0; done < n_layers; done += kMaxGroupLayers) {
+    const int count = n_layers - done < kMaxGroupLayers ? n_layers - done : kMaxGroupLayers;
+    const int rc = compact_layers(c, first_layer + done, count, nullptr, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+  }
+  return KVP_OK;
+}
+
 int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const void* const* q,
                       const void* const* k, const void* const* v, void* const* out, int32_t scoring,
                       const void* const* q_obs, int32_t n_obs, void* stream, void* side_stream) {

@@ -569,6 +569,64 @@ def test_compaction_on_a_second_stream_changes_nothing(name, sets, scoring):
                                y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
 
 
+@pytest.mark.parametrize("name,layers,scoring", [("tiled_image", 8, "own"), ("video", 5, "own"), ("video", 16, "keydiff"),
+                                                 ("video", 19, "own")])
+def test_compact_layers_is_the_per_layer_compaction(name, layers, scoring):
+    """A model runs its layers one after the other: kvp_prefill_chunk per layer while the block
+    moves up the stack, then ONE kvp_compact_layers for all of them (grouped launches, 16 layers at
+    a time; 19 layers make it a group of 16 and one of 3; in the five-layer case one layer is held a
+    block behind, which makes the range inhomogeneous).  Caches and outputs must be those of the call-by-call order, bit for bit."""
+    wl = get_workload(name)
+    data = [tuple(U.bits_to_torch(x) for x in layer_inputs(wl, l)) for l in range(layers)]
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    results = []
+    for grouped in (False, True):
+        cache = K.Cache(layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments,
+                        merge=True, scratch_sets=layers if grouped else 1, device=DEV)
+        outs = [torch.zeros((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=DEV)
+                for _ in range(layers)]
+        lag = layers - 2 if name == "video" and layers == 5 else -1      # this layer gets its blocks one call late
+        pending_lag = None
+        for t0, n in ranges:
+            for l in range(layers):
+                if l == lag:
+                    continue
+                q, k, v = (x[t0:t0 + n] for x in data[l])
+                if scoring == "keydiff":
+                    cache.prefill_chunk_keydiff(l, t0, q, k, v, out=outs[l][:n])
+                else:
+                    cache.prefill_chunk(l, t0, q, k, v, out=outs[l][:n])
+                if not grouped:
+                    cache.compact(l)
+            if lag >= 0:
+                if pending_lag is not None:
+                    pt0, pn = pending_lag
+                    q, k, v = (x[pt0:pt0 + pn] for x in data[lag])
+                    cache.prefill_chunk(lag, pt0, q, k, v, out=outs[lag][:pn])
+                    if not grouped:
+                        cache.compact(lag)
+                pending_lag = (t0, n)
+            if grouped:
+                if lag >= 0 and pending_lag == ranges[0]:        # the lagging layer has nothing pending yet
+                    cache.compact_layers(0, lag)
+                    cache.compact_layers(lag + 1, layers - lag - 1)
+                else:
+                    cache.compact_layers(0, layers)
+        torch.cuda.synchronize()
+        state = []
+        for l in range(layers):
+            k, v, idx, w, count, nxt = cache.decode_ready(l)
+            state.append((k[:, :count].clone(), v[:, :count].clone(), idx[:, :count].clone(), w[:, :count].clone(),
+                          count, nxt, outs[l].clone()))
+        results.append(state)
+        cache.close()
+    for a, b in zip(*results):
+        assert a[4] == b[4] and a[5] == b[5]
+        for x, y in zip(a[:4] + (a[6],), b[:4] + (b[6],)):
+            assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                               y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
+
+
 def test_real_cache_refuses_null_tensors():
     """A cache on a live allocation (not a dry run) returns KVP_EINVAL for a null tensor before it
     enqueues anything, and stays usable."""

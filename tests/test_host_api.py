@@ -245,6 +245,41 @@ def test_prefill_block_walks_every_layer():
         K.kvp_free_cache(h)
 
 
+def test_compact_layers_state_machine():
+    """kvp_compact_layers in a dry run: a range of PENDING layers becomes READY with the block
+    appended; a range that holds a layer that is not PENDING, or that is out of bounds, is refused
+    with nothing changed; layers out of step with one another are still all compacted."""
+    wl = get_workload("tiled_image")
+    rc, h = K.kvp_init_cache(_cfg(wl, sets=wl.n_layers), wl.segments, None, 0)
+    assert rc == K.KVP_OK
+    try:
+        nl = wl.n_layers
+        assert K.kvp_compact_layers(None, 0, 1) == K.KVP_EINVAL
+        for first, count in ((-1, 2), (0, 0), (0, nl + 1), (nl - 1, 2), (nl, 1)):
+            assert K.kvp_compact_layers(h, first, count) == K.KVP_EINVAL
+        assert K.kvp_compact_layers(h, 0, nl) == K.KVP_ESTATE                 # nothing pending
+        for layer in range(nl - 1):
+            assert K.kvp_prefill_chunk(h, layer, 0, 24, 0, 0, 0, 0) == K.KVP_OK
+        assert K.kvp_compact_layers(h, 0, nl) == K.KVP_ESTATE                 # the last layer is READY
+        for layer in range(nl - 1):
+            assert K.kvp_decode_ready(h, layer)[0] == K.KVP_ESTATE            # still pending, all of them
+        assert K.kvp_compact_layers(h, 0, nl - 1) == K.KVP_OK
+        for layer in range(nl):
+            rc, vw = K.kvp_decode_ready(h, layer)
+            assert rc == K.KVP_OK and (vw.count, vw.next_token) == ((24, 24) if layer < nl - 1 else (0, 0))
+        # layers out of step with one another (the last one is a block behind): still one call
+        assert K.kvp_prefill_chunk(h, nl - 1, 0, 24, 0, 0, 0, 0) == K.KVP_OK
+        for layer in range(nl - 1):
+            assert K.kvp_prefill_chunk(h, layer, 24, 8, 0, 0, 0, 0) == K.KVP_OK
+        assert K.kvp_compact_layers(h, 0, nl) == K.KVP_OK
+        for layer in range(nl):
+            rc, vw = K.kvp_decode_ready(h, layer)
+            assert rc == K.KVP_OK and vw.next_token == (32 if layer < nl - 1 else 24)
+        assert K.kvp_compact_layers(h, 2, 3) == K.KVP_ESTATE
+    finally:
+        K.kvp_free_cache(h)
+
+
 def test_scratch_sets_gate_pending_layers():
     wl = get_workload("single_image")
     for sets, second_ok in ((1, False), (2, True)):
