@@ -67,6 +67,13 @@ colsum_kernel(const ColsumArgs a) {
   const int xcd = blockIdx.x % kXcds;
   const int w = xcd * a.work_per_xcd + blockIdx.x / kXcds;
   if (w >= a.total_work) return;
+  // grid y: the layer of the group
+  const int li = blockIdx.y;
+  const u16* const q_rows = a.q_layer[li];
+  const u16* const k_new = a.g.k_new[li];
+  const u16* const k_cache = a.k_cache + (long long)li * a.g.kv_stride;
+  const float* const lse2 = in_set_of(a.lse2, a.g, li);
+  float* const partial = in_set_of(a.partial, a.g, li);
   const int hk = w / a.wgs_per_head;
   const int rem = w % a.wgs_per_head;
   int kvb = 0;
@@ -106,14 +113,14 @@ colsum_kernel(const ColsumArgs a) {
       const int ld_row = kRowsPerInstr * piece + ld_sub;
       const int ld_chunk = ld_pos ^ (ld_row % kChunks);
       const int row = min(qt * 32 + ld_row, n - 1);
-      const u16* src = a.q + ((size_t)row * a.n_q_heads + h) * D + 8 * ld_chunk;
+      const u16* src = q_rows + ((size_t)row * a.n_q_heads + h) * D + 8 * ld_chunk;
       const unsigned dst = __builtin_amdgcn_readfirstlane(
           (unsigned)(size_t)(__attribute__((address_space(3))) void*)(&q_lds[iq_buf][kRowsPerInstr * piece * D]));
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst) : "m0", "memory");
     }
     {
       const int row = min(qt * 32 + l32, n - 1);
-      const float* src = a.lse2 + (size_t)h * a.lse_stride + row;
+      const float* src = lse2 + (size_t)h * a.lse_stride + row;
       const unsigned dst = __builtin_amdgcn_readfirstlane(
           (unsigned)(size_t)(__attribute__((address_space(3))) void*)(&lse_lds[iq_stat][0]));
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(dst) : "m0", "memory");
@@ -134,8 +141,8 @@ colsum_kernel(const ColsumArgs a) {
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int kv = min(key0 + 32 * t + l32, n_cand - 1);     // columns past the end are not stored
-    const u16* src = kv < c ? a.k_cache + ((size_t)hk * a.budget + kv) * D
-                            : a.k_new + ((size_t)(kv - c) * a.n_kv_heads + hk) * D;
+    const u16* src = kv < c ? k_cache + ((size_t)hk * a.budget + kv) * D
+                            : k_new + ((size_t)(kv - c) * a.n_kv_heads + hk) * D;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       kf[t][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + 16 * s + 8 * g));
@@ -307,7 +314,7 @@ colsum_kernel(const ColsumArgs a) {
   }
 
   // lanes l and l + 32 hold the two halves of the rows of one key column
-  float* dstp = a.partial + ((size_t)hk * a.n_partials + split) * a.cand_stride;
+  float* dstp = partial + ((size_t)hk * a.n_partials + split) * a.cand_stride;
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const float mine = colacc[t][0] + colacc[t][1];
@@ -318,7 +325,7 @@ colsum_kernel(const ColsumArgs a) {
   // a key block with fewer row splits than the launch's partial count leaves the rest at zero
   if (split == 0) {
     for (int p = splits + g; p < a.n_partials; p += 2) {
-      float* z = a.partial + ((size_t)hk * a.n_partials + p) * a.cand_stride;
+      float* z = partial + ((size_t)hk * a.n_partials + p) * a.cand_stride;
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int kv = key0 + 32 * t + l32;
@@ -331,8 +338,9 @@ colsum_kernel(const ColsumArgs a) {
 }  // namespace
 
 hipError_t launch_colsum(const ColsumArgs& a, int head_dim, hipStream_t s) {
+  if (a.g.n_layers < 1 || a.g.n_layers > kMaxGroupLayers) return hipErrorInvalidValue;
   const int grid = kXcds * a.work_per_xcd;
-  const dim3 g(grid), b(64 * kColsumWaves);
+  const dim3 g(grid, a.g.n_layers), b(64 * kColsumWaves);
   if (head_dim == 128) {
     if (a.subtiles == 2) hipLaunchKernelGGL((colsum_kernel<128, 2, kColsumWaves>), g, b, 0, s, a);
     else hipLaunchKernelGGL((colsum_kernel<128, 1, kColsumWaves>), g, b, 0, s, a);

@@ -42,13 +42,6 @@ struct Lanes {
   static constexpr int kPairsPerBlock = kThreads / kPerPair;
 };
 
-// the same pointer in scratch set (first_set + li) % n_sets instead of set first_set
-template <class T>
-__device__ __forceinline__ T* in_set_of(T* p, const LayerGroup& g, int li) {
-  const long long sets = (long long)((g.first_set + li) % g.n_sets) - g.first_set;
-  return reinterpret_cast<T*>(reinterpret_cast<uintptr_t>(p) + (uintptr_t)(sets * g.set_stride));
-}
-
 template <int D>
 __global__ void __launch_bounds__(kThreads)
 merge_kernel(const CompactArgs a) {

@@ -21,9 +21,10 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kSliceKeys = kKeydiffSliceKeys;   // keys per workgroup of the sum kernel
 
-__device__ __forceinline__ const u16* key_row(const KeydiffArgs& a, int hk, int kv, int D) {
-  return kv < a.c ? a.k_cache + ((size_t)hk * a.budget + kv) * D
-                  : a.k_new + ((size_t)(kv - a.c) * a.n_kv_heads + hk) * D;
+// candidate kv of KV head hk of layer li of the group: a cache entry or a block key
+__device__ __forceinline__ const u16* key_row(const KeydiffArgs& a, int li, int hk, int kv, int D) {
+  return kv < a.c ? a.k_cache + (long long)li * a.g.kv_stride + ((size_t)hk * a.budget + kv) * D
+                  : a.g.k_new[li] + ((size_t)(kv - a.c) * a.n_kv_heads + hk) * D;
 }
 
 __device__ __forceinline__ void add8(float (&acc)[8], const uint4 w) {
@@ -33,14 +34,14 @@ __device__ __forceinline__ void add8(float (&acc)[8], const uint4 w) {
   acc[6] += __uint_as_float(w.w << 16); acc[7] += __uint_as_float(w.w & 0xFFFF0000u);
 }
 
-// grid (slices, Hkv); thread t: the 16-byte piece t % (D / 8) of rows t / (D / 8) + k * kRowsAtOnce.
+// grid (slices, Hkv, layers of the group); thread t: the 16-byte piece t % (D / 8) of rows t / (D / 8) + k * kRowsAtOnce.
 // All loads of a thread are independent and issued together: one trip to memory per workgroup.
 template <int D>
 __global__ void __launch_bounds__(kThreads)
 keydiff_sum_kernel(const KeydiffArgs a) {
   constexpr int kPieces = D / 8, kRowsAtOnce = kThreads / kPieces, kLoads = kSliceKeys / kRowsAtOnce;
   __shared__ float s_part[kRowsAtOnce][D];
-  const int slice = blockIdx.x, hk = blockIdx.y;
+  const int slice = blockIdx.x, hk = blockIdx.y, li = blockIdx.z;
   const int piece = threadIdx.x % kPieces, rr = threadIdx.x / kPieces;
   const int n_cand = a.c + a.n_keys;
   const int k0 = slice * kSliceKeys;
@@ -48,7 +49,7 @@ keydiff_sum_kernel(const KeydiffArgs a) {
 #pragma unroll
   for (int k = 0; k < kLoads; ++k) {
     const int kv = k0 + rr + k * kRowsAtOnce;
-    w[k] = kv < n_cand ? *reinterpret_cast<const uint4*>(key_row(a, hk, kv, D) + 8 * piece) : uint4{0u, 0u, 0u, 0u};
+    w[k] = kv < n_cand ? *reinterpret_cast<const uint4*>(key_row(a, li, hk, kv, D) + 8 * piece) : uint4{0u, 0u, 0u, 0u};
   }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -60,11 +61,11 @@ keydiff_sum_kernel(const KeydiffArgs a) {
     float t = 0.f;
 #pragma unroll
     for (int r = 0; r < kRowsAtOnce; ++r) t += s_part[r][threadIdx.x];
-    a.sums[((size_t)hk * a.n_slices + slice) * D + threadIdx.x] = t;
+    in_set_of(a.sums, a.g, li)[((size_t)hk * a.n_slices + slice) * D + threadIdx.x] = t;
   }
 }
 
-// grid (blocks of 64 keys, Hkv); four lanes per key, 16 keys per wave
+// grid (blocks of 64 keys, Hkv, layers of the group); four lanes per key, 16 keys per wave
 template <int D>
 __global__ void __launch_bounds__(kThreads)
 keydiff_score_kernel(const KeydiffArgs a) {
@@ -72,7 +73,8 @@ keydiff_score_kernel(const KeydiffArgs a) {
   __shared__ __align__(16) float s_mu[D];
   __shared__ float s_fold[kFold][D];
   __shared__ float s_mu2;
-  const int hk = blockIdx.y;
+  const int hk = blockIdx.y, li = blockIdx.z;
+  const float* const sums = in_set_of(a.sums, a.g, li);
   const int n_cand = a.c + a.n_keys;
   // this thread's piece of its key first: the load is on its way while the anchor is folded
   constexpr int kPer = D / 4;                      // channels per lane: a quarter of a key
@@ -80,7 +82,7 @@ keydiff_score_kernel(const KeydiffArgs a) {
   const int quarter = threadIdx.x & 3;
   uint4 kw[kPer / 8];
   if (kv < n_cand) {
-    const u16* row = key_row(a, hk, kv, D) + kPer * quarter;
+    const u16* row = key_row(a, li, hk, kv, D) + kPer * quarter;
 #pragma unroll
     for (int i = 0; i < kPer / 8; ++i) kw[i] = *reinterpret_cast<const uint4*>(row + 8 * i);
   }
@@ -91,7 +93,7 @@ keydiff_score_kernel(const KeydiffArgs a) {
     const int s0 = part * per, s1 = min(a.n_slices, s0 + per);
     float t = 0.f;
 #pragma unroll 8
-    for (int s2 = s0; s2 < s1; ++s2) t += a.sums[((size_t)hk * a.n_slices + s2) * D + ch];
+    for (int s2 = s0; s2 < s1; ++s2) t += sums[((size_t)hk * a.n_slices + s2) * D + ch];
     s_fold[part][ch] = t;
   }
   __syncthreads();
@@ -127,7 +129,7 @@ keydiff_score_kernel(const KeydiffArgs a) {
   dot += __shfl_xor(dot, 1, 64); k2 += __shfl_xor(k2, 1, 64);
   dot += __shfl_xor(dot, 2, 64); k2 += __shfl_xor(k2, 2, 64);
   if (quarter == 0 && kv < n_cand)
-    a.scores[(size_t)hk * a.cand_stride + kv] = -dot / (sqrtf(k2) * sqrtf(s_mu2));
+    in_set_of(a.scores, a.g, li)[(size_t)hk * a.cand_stride + kv] = -dot / (sqrtf(k2) * sqrtf(s_mu2));
 }
 
 }  // namespace
@@ -136,7 +138,9 @@ hipError_t launch_keydiff(KeydiffArgs a, int head_dim, hipStream_t s) {
   const int n_cand = a.c + a.n_keys;
   a.n_slices = keydiff_slices(n_cand);
   a.keys_per_block = 64;
-  const dim3 g1(a.n_slices, a.n_kv_heads), g2((n_cand + a.keys_per_block - 1) / a.keys_per_block, a.n_kv_heads);
+  if (a.g.n_layers < 1 || a.g.n_layers > kMaxGroupLayers) return hipErrorInvalidValue;
+  const dim3 g1(a.n_slices, a.n_kv_heads, a.g.n_layers);
+  const dim3 g2((n_cand + a.keys_per_block - 1) / a.keys_per_block, a.n_kv_heads, a.g.n_layers);
   if (head_dim == 128) {
     hipLaunchKernelGGL(keydiff_sum_kernel<128>, g1, dim3(kThreads), 0, s, a);
     hipLaunchKernelGGL(keydiff_score_kernel<128>, g2, dim3(kThreads), 0, s, a);

@@ -90,6 +90,7 @@ Layout make_layout(const kvp_config& c) {
 }
 
 enum LayerState { READY = 0, PENDING = 1 };
+enum { kScoreOwn = 0, kScoreProxy = 1, kScoreKeydiff = 2 };
 
 struct Layer {
   int state = READY;
@@ -100,6 +101,12 @@ struct Layer {
   int n_partials = 0;   // partial score arrays the scoring pass of the pending block left
   const u16* k = nullptr;
   const u16* v = nullptr;
+  // a scoring pass (proxy queries, or the keys alone) that is still to be launched:
+  // kvp_prefill_block launches it for a group of layers at once; a layer in this state cannot be
+  // compacted yet
+  const u16* q_obs = nullptr;
+  int n_obs = 0;
+  int unscored = 0;     // 0, kScoreProxy or kScoreKeydiff
   // last block, for kvp_debug_last
   int last_cand = 0;
   bool has_last = false;
@@ -173,15 +180,9 @@ int launch(kvp_cache* c, int kind, int layers, hipStream_t s, F&& f) {
   return KVP_OK;
 }
 
-// Alg. 1 lines 7-11 for `count` consecutive layers that hold the same block (same entries in the
-// cache, same tokens pending): one launch of each compaction kernel for all of them.
-int run_compact(kvp_cache* c, int first, int count, const float* scores_override, hipStream_t s) {
-  Layer& L = c->layers[first];
-  const kvp_config& cfg = c->cfg;
+// `count` consecutive layers from `first` on, each with its pending block, as the kernels see them
+LayerGroup make_group(const kvp_cache* c, int first, int count) {
   const Layout& lay = c->lay;
-  unsigned char* set = c->set(first);
-  const int cnt = L.count, n = L.n, M = cfg.budget;
-
   LayerGroup g{};
   g.n_layers = count;
   g.first_set = first % lay.n_sets;
@@ -193,6 +194,19 @@ int run_compact(kvp_cache* c, int first, int count, const float* scores_override
     g.k_new[i] = c->layers[first + i].k;
     g.v_new[i] = c->layers[first + i].v;
   }
+  return g;
+}
+
+// Alg. 1 lines 7-11 for `count` consecutive layers that hold the same block (same entries in the
+// cache, same tokens pending): one launch of each compaction kernel for all of them.
+int run_compact(kvp_cache* c, int first, int count, const float* scores_override, hipStream_t s) {
+  Layer& L = c->layers[first];
+  const kvp_config& cfg = c->cfg;
+  const Layout& lay = c->lay;
+  unsigned char* set = c->set(first);
+  const int cnt = L.count, n = L.n, M = cfg.budget;
+
+  const LayerGroup g = make_group(c, first, count);
 
   CompactArgs ca{};
   ca.g = g;
@@ -258,7 +272,7 @@ int run_compact(kvp_cache* c, int first, int count, const float* scores_override
 // one layer at a time otherwise.  Every layer must be PENDING.
 int compact_layers(kvp_cache* c, int first, int count, const float* scores_override, hipStream_t s) {
   for (int i = 0; i < count; ++i)
-    if (c->layers[first + i].state != PENDING) return KVP_ESTATE;
+    if (c->layers[first + i].state != PENDING || c->layers[first + i].unscored != 0) return KVP_ESTATE;
   bool same = count <= kMaxGroupLayers && (scores_override == nullptr || count == 1);
   const Layer& A = c->layers[first];
   for (int i = 1; i < count && same; ++i) {
@@ -380,13 +394,121 @@ int kvp_init_cache(const kvp_config* cfg, const kvp_segment* segs, int32_t n_seg
 
 namespace {
 
-enum { kScoreOwn = 0, kScoreProxy = 1, kScoreKeydiff = 2 };
+
+// A short list of proxy queries would leave the attention kernel with a handful of workgroups that
+// each walk all keys: rowstat_kernel spreads the keys instead.  Its per-block partials borrow the
+// memory of the column-sum partials, which the scoring pass only writes afterwards.
+bool proxy_by_rowstat(const kvp_cache* c, int n_cand, int n_obs) {
+  const kvp_config& cfg = c->cfg;
+  const Layout& lay = c->lay;
+  const int n_kb = rowstat_key_blocks(n_cand);
+  const size_t need = (size_t)cfg.n_q_heads * n_obs * n_kb * 2 * sizeof(float);
+  const size_t have = (size_t)cfg.n_kv_heads * lay.max_partials * lay.cand_stride * sizeof(float);
+  return (long long)n_obs * cfg.n_q_heads < 128 * 64 && need <= have;
+}
+
+// The scoring kernels' arguments for `layer` (the first layer of a group, or the only one) with
+// `count` entries in its cache and a block of `n_tokens`; the group and the queries are the caller's.
+RowstatArgs rowstat_args(kvp_cache* c, int layer, int count, int n_tokens, int n_obs) {
+  const kvp_config& cfg = c->cfg;
+  const Layout& lay = c->lay;
+  unsigned char* set = c->set(layer);
+  RowstatArgs ra{};
+  ra.k_cache = c->k_cache(layer);
+  ra.lse2 = reinterpret_cast<float*>(set + lay.lse_off);
+  ra.part_m = reinterpret_cast<float*>(set + lay.partial_off);
+  ra.part_l = ra.part_m + (size_t)cfg.n_q_heads * n_obs * rowstat_key_blocks(count + n_tokens);
+  ra.n = n_obs; ra.c = count; ra.n_keys = n_tokens;
+  ra.n_q_heads = cfg.n_q_heads; ra.n_kv_heads = cfg.n_kv_heads;
+  ra.budget = cfg.budget; ra.lse_stride = cfg.chunk_max;
+  ra.scale_log2 = c->scale * 1.4426950408889634f;
+  return ra;
+}
+
+ColsumArgs colsum_args(kvp_cache* c, int layer, int count, int n_tokens, int n_rows, int shift) {
+  const kvp_config& cfg = c->cfg;
+  const Layout& lay = c->lay;
+  unsigned char* set = c->set(layer);
+  ColsumArgs cs{};
+  cs.k_cache = c->k_cache(layer);
+  cs.lse2 = reinterpret_cast<float*>(set + lay.lse_off);
+  cs.partial = reinterpret_cast<float*>(set + lay.partial_off);
+  cs.n = n_rows; cs.c = count;
+  cs.n_keys = n_tokens; cs.shift = shift;
+  cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
+  cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
+  cs.scale_log2 = c->scale * 1.4426950408889634f;
+  plan_colsum(cs, cfg.head_dim);
+  return cs;
+}
+
+KeydiffArgs keydiff_args(kvp_cache* c, int layer, int count, int n_tokens) {
+  const kvp_config& cfg = c->cfg;
+  const Layout& lay = c->lay;
+  KeydiffArgs ka{};
+  ka.k_cache = c->k_cache(layer);
+  ka.scores = reinterpret_cast<float*>(c->set(layer) + lay.partial_off);          // the one "partial"
+  ka.sums = ka.scores + (size_t)cfg.n_kv_heads * lay.cand_stride;
+  ka.c = count; ka.n_keys = n_tokens; ka.n_kv_heads = cfg.n_kv_heads;
+  ka.budget = cfg.budget; ka.cand_stride = lay.cand_stride;
+  return ka;
+}
+
+// The scoring pass (proxy queries: row statistics, then column sums; or the keys alone) for `count`
+// consecutive layers whose blocks went through prefill_impl with `defer`: one launch of each
+// kernel for up to kMaxGroupLayers layers in the same state, else layer by layer.
+int score_deferred_layers(kvp_cache* c, int first, int count, hipStream_t s) {
+  const kvp_config& cfg = c->cfg;
+  for (int done = 0; done < count;) {
+    Layer& A = c->layers[first + done];
+    if (A.unscored == 0) {          // scored inside prefill_impl already (nothing to evict, or a long list)
+      ++done;
+      continue;
+    }
+    int m = 1;
+    while (done + m < count && m < kMaxGroupLayers) {
+      const Layer& B = c->layers[first + done + m];
+      if (B.unscored != A.unscored || B.count != A.count || B.n != A.n || B.t0 != A.t0 || B.n_obs != A.n_obs) break;
+      ++m;
+    }
+    const int layer = first + done;
+    const LayerGroup g = make_group(c, layer, m);
+    int n_partials = 1;
+    if (A.unscored == kScoreKeydiff) {
+      KeydiffArgs ka = keydiff_args(c, layer, A.count, A.n);
+      ka.g = g;
+      const int rc = launch(c, KVP_K_KEYDIFF, m, s, [&] { return launch_keydiff(ka, cfg.head_dim, s); });
+      if (rc) return rc;
+    } else {
+      RowstatArgs ra = rowstat_args(c, layer, A.count, A.n, A.n_obs);
+      ColsumArgs cs = colsum_args(c, layer, A.count, A.n, A.n_obs, A.n);
+      ra.g = g;
+      cs.g = g;
+      for (int i = 0; i < m; ++i) ra.q_layer[i] = cs.q_layer[i] = c->layers[layer + i].q_obs;
+      int rc = launch(c, KVP_K_ROWSTAT, m, s, [&] { return launch_rowstat(ra, cfg.head_dim, s); });
+      if (rc) return rc;
+      rc = launch(c, KVP_K_COLSUM, m, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
+      if (rc) return rc;
+      n_partials = cs.n_partials;
+    }
+    for (int i = 0; i < m; ++i) {
+      Layer& L = c->layers[layer + i];
+      L.n_partials = n_partials;
+      L.unscored = 0;
+    }
+    done += m;
+  }
+  return KVP_OK;
+}
 
 // kvp_prefill_chunk and its variants: attention for the block; the scores come from the block's
 // own queries, from proxy queries, or from the keys alone
+// `defer`: leave the scoring pass of proxy queries or of the keys alone to score_deferred_layers,
+// which launches it for a group of layers at once (kvp_prefill_block); the layer is PENDING and
+// `unscored` until then.
 int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
                  const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs, int mode,
-                 void* stream) {
+                 void* stream, bool defer = false) {
   const bool proxy = mode == kScoreProxy;
   if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
   if (n_tokens < 1 || n_tokens > c->cfg.chunk_max) return KVP_EINVAL;
@@ -432,9 +554,16 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
   int rc = launch(c, KVP_K_ATTENTION, 1, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
   if (rc) return rc;
   aa.partial = nullptr;
+  L.unscored = 0;
   if (fused) {
     L.n_partials = own_partials;
   } else if (evicts) {
+    // the block as the scoring kernels see it: this layer alone
+    LayerGroup one{};
+    one.n_layers = 1;
+    one.first_set = set_i; one.n_sets = lay.n_sets;
+    one.k_new[0] = aa.k_new; one.v_new[0] = aa.v_new;
+    bool deferred = false;
     if (proxy) {
       // row statistics of the proxy queries over all candidates (nothing hidden, no output);
       // they replace the block's own in the scratch set
@@ -442,48 +571,37 @@ int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tok
       aa.out = nullptr;
       aa.n = n_obs;
       aa.shift = n_tokens;
-      // a short list of proxy queries would leave the attention kernel with a handful of
-      // workgroups: spread the keys instead.  The per-block partials borrow the memory of the
-      // column-sum partials, which the scoring pass only writes afterwards.
-      const int n_kb = rowstat_key_blocks(L.count + n_tokens);
-      const size_t need = (size_t)cfg.n_q_heads * n_obs * n_kb * 2 * sizeof(float);
-      const size_t have = (size_t)cfg.n_kv_heads * lay.max_partials * lay.cand_stride * sizeof(float);
-      if ((long long)n_obs * cfg.n_q_heads < 128 * 64 && need <= have) {
-        RowstatArgs ra{};
-        ra.q = aa.q; ra.k_new = aa.k_new; ra.k_cache = aa.k_cache; ra.lse2 = aa.lse2;
-        ra.part_m = reinterpret_cast<float*>(set + lay.partial_off);
-        ra.part_l = ra.part_m + (size_t)cfg.n_q_heads * n_obs * n_kb;
-        ra.n = n_obs; ra.c = L.count; ra.n_keys = n_tokens;
-        ra.n_q_heads = cfg.n_q_heads; ra.n_kv_heads = cfg.n_kv_heads;
-        ra.budget = cfg.budget; ra.lse_stride = cfg.chunk_max;
-        ra.scale_log2 = aa.scale_log2;
-        rc = launch(c, KVP_K_ROWSTAT, 1, s, [&] { return launch_rowstat(ra, cfg.head_dim, s); });
+      if (proxy_by_rowstat(c, L.count + n_tokens, n_obs)) {
+        if (defer) {
+          deferred = true;
+        } else {
+          RowstatArgs ra = rowstat_args(c, layer, L.count, n_tokens, n_obs);
+          ra.g = one;
+          ra.q_layer[0] = aa.q;
+          rc = launch(c, KVP_K_ROWSTAT, 1, s, [&] { return launch_rowstat(ra, cfg.head_dim, s); });
+        }
       } else {
         plan_attention(aa, cfg.head_dim, c->attn_shape);
         rc = launch(c, KVP_K_ATTENTION, 1, s, [&] { return launch_attention(aa, cfg.head_dim, s); });
       }
       if (rc) return rc;
     }
-    if (mode == kScoreKeydiff) {
-      KeydiffArgs ka{};
-      ka.k_new = aa.k_new; ka.k_cache = aa.k_cache;
-      ka.scores = reinterpret_cast<float*>(set + lay.partial_off);          // the one "partial"
-      ka.sums = ka.scores + (size_t)cfg.n_kv_heads * lay.cand_stride;
-      ka.c = L.count; ka.n_keys = n_tokens; ka.n_kv_heads = cfg.n_kv_heads;
-      ka.budget = cfg.budget; ka.cand_stride = lay.cand_stride;
+    if (deferred) {
+      L.q_obs = aa.q;
+      L.n_obs = n_obs;
+      L.unscored = kScoreProxy;
+    } else if (mode == kScoreKeydiff && defer) {
+      L.unscored = kScoreKeydiff;
+    } else if (mode == kScoreKeydiff) {
+      KeydiffArgs ka = keydiff_args(c, layer, L.count, n_tokens);
+      ka.g = one;
       rc = launch(c, KVP_K_KEYDIFF, 1, s, [&] { return launch_keydiff(ka, cfg.head_dim, s); });
       if (rc) return rc;
       L.n_partials = 1;
     } else {
-      ColsumArgs cs{};
-      cs.q = aa.q; cs.k_new = aa.k_new; cs.k_cache = aa.k_cache; cs.lse2 = aa.lse2;
-      cs.partial = reinterpret_cast<float*>(set + lay.partial_off);
-      cs.n = aa.n; cs.c = L.count;
-      cs.n_keys = n_tokens; cs.shift = aa.shift;
-      cs.n_q_heads = cfg.n_q_heads; cs.n_kv_heads = cfg.n_kv_heads;
-      cs.budget = cfg.budget; cs.lse_stride = cfg.chunk_max; cs.cand_stride = lay.cand_stride;
-      cs.scale_log2 = aa.scale_log2;
-      plan_colsum(cs, cfg.head_dim);
+      ColsumArgs cs = colsum_args(c, layer, L.count, n_tokens, aa.n, aa.shift);
+      cs.g = one;
+      cs.q_layer[0] = aa.q;
       rc = launch(c, KVP_K_COLSUM, 1, s, [&] { return launch_colsum(cs, cfg.head_dim, s); });
       if (rc) return rc;
       L.n_partials = cs.n_partials;
@@ -580,11 +698,15 @@ int kvp_prefill_block(kvp_cache* c, int32_t token_begin, int32_t n_tokens, const
     int rc = KVP_OK;
     for (int layer = first; layer < last; ++layer) {
       rc = prefill_impl(c, layer, token_begin, n_tokens, q[layer], k[layer], v[layer], out[layer],
-                        mode == kScoreProxy ? q_obs[layer] : nullptr, n_obs, mode, stream);
+                        mode == kScoreProxy ? q_obs[layer] : nullptr, n_obs, mode, stream, mode != kScoreOwn);
       if (rc) {
         last = layer;                            // the layers before it still get their compaction
         break;
       }
+    }
+    if (mode != kScoreOwn && last > first) {
+      const int rc3 = score_deferred_layers(c, first, last - first, main);
+      if (rc3) return rc3;
     }
     const size_t slot = (size_t)(c->n_groups % ring);
     if (two && last > first) {
@@ -699,6 +821,7 @@ int kvp_set_state(kvp_cache* c, int32_t layer, int32_t count, int32_t next_token
   const int set_i = layer % c->lay.n_sets;
   if (L.state == PENDING && c->set_owner[set_i] == layer) c->set_owner[set_i] = -1;
   L.state = READY;
+  L.unscored = 0;
   L.count = count;
   L.next_token = next_token;
   L.has_last = false;

@@ -53,14 +53,41 @@ struct AttnArgs {
   float scale_log2;    // softmax scale times log2(e)
 };
 
+// A launch of the selection and compaction kernels covers a group of consecutive layers that hold
+// the same block (same c, n, t0).  The pointers in SelectArgs and CompactArgs are those of the
+// group's FIRST layer; layer i of the group is reached through the strides below.
+constexpr int kMaxGroupLayers = 16;
+struct LayerGroup {
+  int n_layers;
+  int first_set, n_sets;        // layer i uses scratch set (first_set + i) % n_sets
+  long long set_stride;         // bytes between scratch sets
+  long long kv_stride;          // bf16 elements between the K (or V) caches of consecutive layers
+  long long meta_stride;        // elements between their token_idx (or weight) arrays
+  const u16* k_new[kMaxGroupLayers];   // the block's keys and values of every layer of the group
+  const u16* v_new[kMaxGroupLayers];
+};
+
+#if defined(__HIPCC__)
+// the same pointer in scratch set (first_set + li) % n_sets instead of set first_set
+template <class T>
+__device__ __forceinline__ T* in_set_of(T* p, const LayerGroup& g, int li) {
+  if (p == nullptr) return p;
+  const long long sets = (long long)((g.first_set + li) % g.n_sets) - g.first_set;
+  return reinterpret_cast<T*>(reinterpret_cast<uintptr_t>(p) + (uintptr_t)(sets * g.set_stride));
+}
+#endif
+
 // Column sums of the softmax matrix (Eq. 4 summed over rows and over the query
 // heads of a KV group), one partial array per row split.
 constexpr int kColsumMaxKvBlocks = 64;
 struct ColsumArgs {
-  const u16* q;
-  const u16* k_new;
-  const u16* k_cache;
-  const float* lse2;
+  // One launch scores a group of layers (grid y = layer): layer i of the group reads its queries
+  // from q_layer[i], the block's keys from g.k_new[i], the cache g.kv_stride elements further on
+  // per layer, and its statistics and partials from scratch set (g.first_set + i) % g.n_sets.
+  LayerGroup g;
+  const u16* q_layer[kMaxGroupLayers];
+  const u16* k_cache;  // of the group's first layer
+  const float* lse2;   // in the first layer's scratch set, like partial
   float* partial;      // [Hkv, n_partials, cand_stride]
   int n, c, n_q_heads, n_kv_heads, budget, lse_stride, cand_stride;
   int n_keys, shift;   // as in AttnArgs
@@ -77,9 +104,9 @@ struct ColsumArgs {
 
 // Row statistics of a short list of proxy queries over all candidates (rowstat.hip).
 struct RowstatArgs {
-  const u16* q;        // [n, Hq, D] proxy queries
-  const u16* k_new;    // [n_keys, Hkv, D]
-  const u16* k_cache;  // this layer: [Hkv, M, D]
+  LayerGroup g;        // a group of layers per launch, as in ColsumArgs; g.k_new[i]: [n_keys, Hkv, D]
+  const u16* q_layer[kMaxGroupLayers];   // [n, Hq, D] proxy queries of every layer of the group
+  const u16* k_cache;  // the group's first layer: [Hkv, M, D]
   float* lse2;         // [Hq, lse_stride] out
   float* part_m;       // [Hq, n, n_kv_blocks] scratch: row maximum per key block (raw logits)
   float* part_l;       // [Hq, n, n_kv_blocks] scratch: sum of exp2 against that maximum
@@ -92,10 +119,10 @@ hipError_t launch_rowstat(RowstatArgs a, int head_dim, hipStream_t s);
 
 // Query-agnostic scores of all candidates (keydiff.hip).
 struct KeydiffArgs {
-  const u16* k_new;    // [n_keys, Hkv, D]
-  const u16* k_cache;  // this layer: [Hkv, M, D]
+  LayerGroup g;        // a group of layers per launch (grid z); g.k_new[i]: [n_keys, Hkv, D]
+  const u16* k_cache;  // the group's first layer: [Hkv, M, D]
   float* sums;         // [Hkv, n_slices, D] scratch: column sums of the keys, one per slice
-  float* scores;       // [Hkv, cand_stride] out
+  float* scores;       // [Hkv, cand_stride] out (both in the first layer's scratch set)
   int c, n_keys, n_kv_heads, budget, cand_stride;
   int n_slices, keys_per_block;   // set by launch_keydiff
 };
@@ -144,19 +171,6 @@ struct DstEntry {
   int src[kNeighbours];     // candidate positions of its sources
 };
 
-// A launch of the selection and compaction kernels covers a group of consecutive layers that hold
-// the same block (same c, n, t0).  The pointers in SelectArgs and CompactArgs are those of the
-// group's FIRST layer; layer i of the group is reached through the strides below.
-constexpr int kMaxGroupLayers = 16;
-struct LayerGroup {
-  int n_layers;
-  int first_set, n_sets;        // layer i uses scratch set (first_set + i) % n_sets
-  long long set_stride;         // bytes between scratch sets
-  long long kv_stride;          // bf16 elements between the K (or V) caches of consecutive layers
-  long long meta_stride;        // elements between their token_idx (or weight) arrays
-  const u16* k_new[kMaxGroupLayers];   // the block's keys and values of every layer of the group
-  const u16* v_new[kMaxGroupLayers];
-};
 
 struct SelectArgs {
   LayerGroup g;

@@ -36,8 +36,14 @@ rowstat_kernel(const RowstatArgs a) {
   __shared__ float s_m[4][32], s_l[4][32];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  const int kb = blockIdx.x, rt = blockIdx.y, h = blockIdx.z;
+  // grid (key blocks, row tiles, layers of the group x query heads)
+  const int kb = blockIdx.x, rt = blockIdx.y, li = blockIdx.z / a.n_q_heads, h = blockIdx.z % a.n_q_heads;
   const int hk = h / (a.n_q_heads / a.n_kv_heads);
+  const u16* const q_rows = a.q_layer[li];
+  const u16* const k_new = a.g.k_new[li];
+  const u16* const k_cache = a.k_cache + (long long)li * a.g.kv_stride;
+  float* const part_m = in_set_of(a.part_m, a.g, li);
+  float* const part_l = in_set_of(a.part_l, a.g, li);
   const int c = a.c, n_cand = a.c + a.n_keys;
   const int key0 = kb * kBlockKeys + wave * kWaveKeys;
 
@@ -45,7 +51,7 @@ rowstat_kernel(const RowstatArgs a) {
   bf16x8 qf[D / 16];
   {
     const int row = min(32 * rt + l32, a.n - 1);
-    const u16* src = a.q + ((size_t)row * a.n_q_heads + h) * D + 8 * g;
+    const u16* src = q_rows + ((size_t)row * a.n_q_heads + h) * D + 8 * g;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + 16 * s));
   }
@@ -55,8 +61,8 @@ rowstat_kernel(const RowstatArgs a) {
 #pragma unroll
   for (int t = 0; t < kSub; ++t) {
     const int kv = min(key0 + 32 * t + l32, n_cand - 1);
-    const u16* src = (kv < c ? a.k_cache + ((size_t)hk * a.budget + kv) * D
-                             : a.k_new + ((size_t)(kv - c) * a.n_kv_heads + hk) * D) + 8 * g;
+    const u16* src = (kv < c ? k_cache + ((size_t)hk * a.budget + kv) * D
+                             : k_new + ((size_t)(kv - c) * a.n_kv_heads + hk) * D) + 8 * g;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
 #pragma unroll
@@ -92,36 +98,41 @@ rowstat_kernel(const RowstatArgs a) {
     const int row = 32 * rt + tid;
     if (row < a.n) {
       const size_t at = ((size_t)h * a.n + row) * a.n_kv_blocks + kb;
-      a.part_m[at] = mm;
-      a.part_l[at] = ll;
+      part_m[at] = mm;
+      part_l[at] = ll;
     }
   }
 }
 
 // lse2[h][row] from the partials of all key blocks, folded in block order
 __global__ void rowstat_fold_kernel(const RowstatArgs a) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  // grid (blocks of 256 rows, layers of the group)
+  const int i = blockIdx.x * blockDim.x + threadIdx.x, li = blockIdx.y;
   if (i >= a.n_q_heads * a.n) return;
+  const float* const part_m = in_set_of(a.part_m, a.g, li);
+  const float* const part_l = in_set_of(a.part_l, a.g, li);
   const int h = i / a.n, row = i % a.n;
   const size_t at = ((size_t)h * a.n + row) * a.n_kv_blocks;
   float mm = -INFINITY;
-  for (int b = 0; b < a.n_kv_blocks; ++b) mm = fmaxf(mm, a.part_m[at + b]);
+  for (int b = 0; b < a.n_kv_blocks; ++b) mm = fmaxf(mm, part_m[at + b]);
   float ll = 0.f;
-  for (int b = 0; b < a.n_kv_blocks; ++b) ll += a.part_l[at + b] * __builtin_amdgcn_exp2f((a.part_m[at + b] - mm) * a.scale_log2);
-  a.lse2[(size_t)h * a.lse_stride + row] = mm * a.scale_log2 + __builtin_log2f(ll);
+  for (int b = 0; b < a.n_kv_blocks; ++b) ll += part_l[at + b] * __builtin_amdgcn_exp2f((part_m[at + b] - mm) * a.scale_log2);
+  in_set_of(a.lse2, a.g, li)[(size_t)h * a.lse_stride + row] = mm * a.scale_log2 + __builtin_log2f(ll);
 }
 
 }  // namespace
 
 hipError_t launch_rowstat(RowstatArgs a, int head_dim, hipStream_t s) {
   a.n_kv_blocks = rowstat_key_blocks(a.c + a.n_keys);
-  const dim3 grid(a.n_kv_blocks, (a.n + 31) / 32, a.n_q_heads);
+  if (a.g.n_layers < 1 || a.g.n_layers > kMaxGroupLayers || (long long)a.g.n_layers * a.n_q_heads > 65535)
+    return hipErrorInvalidValue;
+  const dim3 grid(a.n_kv_blocks, (a.n + 31) / 32, a.g.n_layers * a.n_q_heads);
   if (head_dim == 128) hipLaunchKernelGGL(rowstat_kernel<128>, grid, dim3(kThreads), 0, s, a);
   else hipLaunchKernelGGL(rowstat_kernel<64>, grid, dim3(kThreads), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int total = a.n_q_heads * a.n;
-  hipLaunchKernelGGL(rowstat_fold_kernel, dim3((total + 255) / 256), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(rowstat_fold_kernel, dim3((total + 255) / 256, a.g.n_layers), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

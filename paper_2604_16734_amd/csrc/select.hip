@@ -129,14 +129,6 @@ __device__ __forceinline__ bool neighbours(const SegL* segs, int n_segs, int tok
 
 // kMaxItems: candidates a thread can own (4 covers up to 4096 candidates and halves the registers
 // of the batched loads; 8 covers the limit)
-// the same pointer in scratch set (first_set + li) % n_sets instead of set first_set
-template <class T>
-__device__ __forceinline__ T* in_set_of(T* p, const LayerGroup& g, int li) {
-  if (p == nullptr) return p;
-  const long long sets = (long long)((g.first_set + li) % g.n_sets) - g.first_set;
-  return reinterpret_cast<T*>(reinterpret_cast<uintptr_t>(p) + (uintptr_t)(sets * g.set_stride));
-}
-
 template <int kMaxItems>
 __global__ void __launch_bounds__(kThreads)
 select_kernel(const SelectArgs a_first) {
