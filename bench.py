@@ -357,8 +357,10 @@ def main():
     ap.add_argument("--workload", default="long_video")
     ap.add_argument("--others", type=int, default=1, help="also time the other four shapes (few steps)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="2: kvp_compact of a layer runs on a second stream beside the next layers' kvp_prefill_chunk")
+    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+                    help="1: everything in line, the compactions of a group of layers after the group's attention "
+                         "launches (measured faster); 2: those compactions on a second stream beside the next "
+                         "group's attention")
     ap.add_argument("--scratch-sets", type=int, default=16,
                     help="scratch sets of the cache: one select/merge/move launch covers a group of layers, "
                          "sets / 2 of them with two streams (two events between the streams per group), "
