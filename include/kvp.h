@@ -180,6 +180,12 @@ int kvp_compact_layers(kvp_cache* cache, int32_t first_layer, int32_t n_layers, 
  *   q, k, v, out, q_obs   HOST arrays of n_layers DEVICE pointers, shapes as for
  *                         the per-layer calls (q_obs only read for KVP_SCORE_PROXY)
  *   scoring               KVP_SCORE_OWN, KVP_SCORE_PROXY or KVP_SCORE_KEYDIFF
+ * The layers go in groups (min(scratch_sets, 16) layers on one stream,
+ * scratch_sets / 2 with a side stream): the attention launches of a group one
+ * after the other, then, each as ONE launch per kernel for the whole group, the
+ * scoring pass of proxy queries or of the keys (the block's own queries are
+ * scored inside the attention launch) and the select, merge and move of the
+ * compaction.  The results are those of the per-layer calls, bit for bit.
  * With side_stream NULL (or equal to stream) everything is enqueued on `stream`
  * in that order.  With another side_stream every kvp_compact goes there, beside
  * the attention of the layers that follow (in a model nothing after a layer's

@@ -86,12 +86,31 @@ int main() {
       for (int l = 0; l < s.layers; ++l) CHECK(kvp_set_state(c, l, 0, 0) == KVP_OK);
       std::vector<const void*> in(s.layers, nullptr);
       std::vector<void*> out(s.layers, nullptr);
-      for (int t0 = 0; t0 < n_tokens; t0 += s.chunk) {
+      int blk = 0;
+      for (int t0 = 0; t0 < n_tokens; t0 += s.chunk, ++blk) {
         const int n = t0 + s.chunk <= n_tokens ? s.chunk : n_tokens - t0;
-        CHECK(kvp_prefill_block(c, t0, n, in.data(), in.data(), in.data(), out.data(), KVP_SCORE_OWN, nullptr, 0,
+        // the three ways of scoring in turn: the proxy and key-only passes go out for a group of layers
+        const int scoring = blk % 3 == 0 ? KVP_SCORE_OWN : blk % 3 == 1 ? KVP_SCORE_PROXY : KVP_SCORE_KEYDIFF;
+        CHECK(kvp_prefill_block(c, t0, n, in.data(), in.data(), in.data(), out.data(), scoring,
+                                scoring == KVP_SCORE_PROXY ? in.data() : nullptr, 1 + blk % s.chunk,
                                 nullptr, nullptr) == KVP_OK);
       }
       CHECK(kvp_prefill_join(c, nullptr, nullptr) == KVP_OK);
+      // and once more layer by layer with one kvp_compact_layers per block, as far as the scratch
+      // sets allow layers to be pending together
+      for (int l = 0; l < s.layers; ++l) CHECK(kvp_set_state(c, l, 0, 0) == KVP_OK);
+      CHECK(kvp_compact_layers(c, 0, s.layers + 1, nullptr) == KVP_EINVAL);
+      CHECK(kvp_compact_layers(c, 0, 1, nullptr) == KVP_ESTATE);
+      for (int t0 = 0; t0 < n_tokens; t0 += s.chunk) {
+        const int n = t0 + s.chunk <= n_tokens ? s.chunk : n_tokens - t0;
+        const int together = sets < s.layers ? sets : s.layers;
+        for (int first = 0; first < s.layers; first += together) {
+          const int count = first + together <= s.layers ? together : s.layers - first;
+          for (int l = first; l < first + count; ++l)
+            CHECK(kvp_prefill_chunk(c, l, t0, n, nullptr, nullptr, nullptr, nullptr, nullptr) == KVP_OK);
+          CHECK(kvp_compact_layers(c, first, count, nullptr) == KVP_OK);
+        }
+      }
       for (int l = 0; l < s.layers; ++l) {
         kvp_view vw{};
         CHECK(kvp_decode_ready(c, l, &vw) == KVP_OK && vw.next_token == n_tokens);
