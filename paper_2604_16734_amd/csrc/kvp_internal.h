@@ -111,7 +111,9 @@ struct RowstatArgs {
   float* part_m;       // [Hq, n, n_kv_blocks] scratch: row maximum per key block (raw logits)
   float* part_l;       // [Hq, n, n_kv_blocks] scratch: sum of exp2 against that maximum
   int n, c, n_keys, n_q_heads, n_kv_heads, budget, lse_stride;
-  int n_kv_blocks;     // set by launch_rowstat
+  int n_kv_blocks;     // set by launch_rowstat, like the next two
+  int items_per_wg;    // (query head, 32-row tile) items a workgroup takes
+  int item_splits;     // workgroups that share the items of a KV head
   float scale_log2;
 };
 int rowstat_key_blocks(int n_cand);
