@@ -275,6 +275,23 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         res["attention_tflops"] = flops_step / (att_ms * 1e-3) / 1e12
         res["attention_plus_scoring_tflops"] = flops_step / ((att_ms + col_ms) * 1e-3) / 1e12
         res["attention_flops_per_launch"] = flops_step / stats["attention"][0] * prof_steps
+        # ---- the same pass with the scores taken by the separate kernel: the attention launch then
+        # holds Eq. 1 alone (what earlier versions of this line reported as the attention roofline)
+        cache.set_score_sweep(0)
+        cache.profile_enable(True)
+        run_steps(K.Prefill(cache, wl.n_layers, overlap=False), cache, wl, data, ranges, prof_steps, outs)
+        torch.cuda.synchronize()
+        alone = cache.profile_read()
+        cache.profile_enable(False)
+        cache.set_score_sweep(1)
+        a_n, a_ms, _ = alone["attention"]
+        c_n, c_ms, _ = alone["colsum"]
+        res["eq1_alone"] = {
+            "avg_launch_us": round(1e3 * a_ms / a_n, 2),
+            "achieved": round(flops_step * prof_steps / (a_ms * 1e-3) / 1e12, 2),
+            "separate_scoring_avg_launch_us": round(1e3 * c_ms / c_n, 2) if c_n else None,
+            "with_separate_scoring_tflops": round(flops_step * prof_steps / ((a_ms + c_ms) * 1e-3) / 1e12, 2),
+        }
         # ---- what the compactions of that pass actually did, and the bytes that takes
         done = {k: v - totals_before[k] for k, v in cache.totals().items()}
         row = wl.head_dim * 2                       # bytes of one K or V row
@@ -493,6 +510,13 @@ def main():
             "mfma_flops_executed_per_launch": executed,
             "executed_tflops": round(executed / (att["avg_us"] * 1e-6) / 1e12, 2),
             "executed_frac": round(executed / (att["avg_us"] * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "note": "the launch holds Eq. 1 AND the second sweep that leaves the scores of Eq. 4; only Eq. 1's flops "
+                    "are counted, so this is the attention-plus-scoring figure. eq1_alone: the same run with the "
+                    "scores taken by the separate kernel instead (kvp_set_score_sweep 0), i.e. the attention launch "
+                    "with Eq. 1 only, and what the two launches reach together",
+            "eq1_alone": dict(main_res["eq1_alone"], unit="TFLOP/s",
+                              frac=round(main_res["eq1_alone"]["achieved"] / PEAK_BF16_TFLOPS, 4),
+                              with_separate_scoring_frac=round(main_res["eq1_alone"]["with_separate_scoring_tflops"] / PEAK_BF16_TFLOPS, 4)),
         },
         "rooflines": rooflines,
         "select_merge_move": {
