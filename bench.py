@@ -275,6 +275,8 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         res["attention_tflops"] = flops_step / (att_ms * 1e-3) / 1e12
         res["attention_plus_scoring_tflops"] = flops_step / ((att_ms + col_ms) * 1e-3) / 1e12
         res["attention_flops_per_launch"] = flops_step / stats["attention"][0] * prof_steps
+        # ---- what the compactions of that pass actually did, and the bytes that takes
+        done = {k: v - totals_before[k] for k, v in cache.totals().items()}
         # ---- the same pass with the scores taken by the separate kernel: the attention launch then
         # holds Eq. 1 alone (what earlier versions of this line reported as the attention roofline)
         cache.set_score_sweep(0)
@@ -292,8 +294,6 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
             "separate_scoring_avg_launch_us": round(1e3 * c_ms / c_n, 2) if c_n else None,
             "with_separate_scoring_tflops": round(flops_step * prof_steps / ((a_ms + c_ms) * 1e-3) / 1e12, 2),
         }
-        # ---- what the compactions of that pass actually did, and the bytes that takes
-        done = {k: v - totals_before[k] for k, v in cache.totals().items()}
         row = wl.head_dim * 2                       # bytes of one K or V row
         appended, select_bytes, colsum_flops, evicting_launches = 0, 0, 0, 0
         c = 0
