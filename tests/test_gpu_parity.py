@@ -161,6 +161,10 @@ def test_scores_and_free_selection(hq, hkv, d, c, n, budget, chunk_max, scale, f
     (32, 8, 128, 2048, 1024, 2048, 1024, 64, 0.0),    # the bench shape with a 64-token prompt
     (2, 2, 64, 6144, 2048, 6144, 2048, 100, 0.0),     # the candidate limit
     (4, 2, 64, 0, 96, 32, 96, 8, 0.0),                # empty cache, block larger than the budget
+    # enough (query head, row tile) items per KV head for the row-statistics kernel to give a
+    # workgroup several of them: 32 items, two per workgroup; 21 items, the last workgroup gets one
+    (16, 2, 64, 6144, 2048, 6144, 2048, 100, 0.0),
+    (28, 4, 64, 6144, 2048, 6144, 2048, 70, 0.0),
 ])
 def test_proxy_query_scores_and_selection(hq, hkv, d, c, n, budget, chunk_max, n_obs, scale):
     """Scores taken with proxy queries (every candidate visible to each of them), the attention
