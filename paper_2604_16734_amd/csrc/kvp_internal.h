@@ -20,7 +20,7 @@ constexpr int kColsumTargetWorkgroups = 512;    // two per CU, all resident: the
 constexpr int kColsumMaxRowSplits = 16;
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectCopies = 32;               // histogram replicas of the radix select
-constexpr int kRowstatBlockKeys = 512;          // keys per workgroup of the proxy row-statistics kernel
+constexpr int kRowstatBlockKeys = 256;          // keys per workgroup of the proxy row-statistics kernel
 constexpr int kKeydiffSliceKeys = 64;           // keys per workgroup of the key-sum kernel
 constexpr int kDecodeTile = 64;                 // keys per workgroup step of the decode kernel
 constexpr int kDecodeMaxSplits = 128;

@@ -4,8 +4,8 @@
 // The attention kernel gives these statistics as a by-product, but it spreads
 // its work over query rows: a few dozen proxy queries would leave most of the
 // chip idle while a handful of workgroups walk all the keys.  Here the keys are
-// spread instead.  A workgroup takes 512 keys of one KV head, which its four
-// waves keep in registers (128 each), and a share of the (query head, 32-row
+// spread instead.  A workgroup takes 256 keys of one KV head, which its four
+// waves keep in registers (64 each), and a share of the (query head, 32-row
 // tile) items of the KV group; per item a wave computes S^T = K Q^T (a lane then
 // holds one query row, its logits in registers), reduces them to (max, sum of
 // exp2) per row, and the four pairs are folded through LDS into one partial per
@@ -24,7 +24,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kSub = 4;                        // 32-key subtiles per wave
+constexpr int kSub = 2;                        // 32-key subtiles per wave
 constexpr int kWaveKeys = 32 * kSub;
 constexpr int kBlockKeys = 4 * kWaveKeys;
 static_assert(kBlockKeys == kRowstatBlockKeys, "the host plans with this block size");
@@ -32,8 +32,8 @@ static_assert(kBlockKeys == kRowstatBlockKeys, "the host plans with this block s
 __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
 
 // grid (key blocks, KV heads x item splits, layers of the group).  An item is one 32-row tile of
-// one query head of the KV group; a workgroup keeps its 512 keys in registers (A operand: a wave
-// its 128) and takes `items_per_wg` items one after the other, the query fragments of the next
+// one query head of the KV group; a workgroup keeps its 256 keys in registers (A operand: a wave
+// its 64) and takes `items_per_wg` items one after the other, the query fragments of the next
 // item on their way while the current one is worked on: every key is fetched once per workgroup
 // instead of once per item.
 template <int D>

@@ -162,7 +162,7 @@ def test_scores_and_free_selection(hq, hkv, d, c, n, budget, chunk_max, scale, f
     (2, 2, 64, 6144, 2048, 6144, 2048, 100, 0.0),     # the candidate limit
     (4, 2, 64, 0, 96, 32, 96, 8, 0.0),                # empty cache, block larger than the budget
     # enough (query head, row tile) items per KV head for the row-statistics kernel to give a
-    # workgroup several of them: 32 items, two per workgroup; 21 items, the last workgroup gets one
+    # workgroup several of them: 32 items in equal shares; 21 items, the last share is a single one
     (16, 2, 64, 6144, 2048, 6144, 2048, 100, 0.0),
     (28, 4, 64, 6144, 2048, 6144, 2048, 70, 0.0),
 ])
