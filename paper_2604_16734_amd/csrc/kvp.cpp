@@ -72,15 +72,22 @@ Layout make_layout(const kvp_config& c) {
   }
   size_t s = 0;
   L.lse_off = s; s = align_up(s + (size_t)c.n_q_heads * B * 4);
-  L.partial_off = s; s = align_up(s + H * L.max_partials * L.cand_stride * 4);
+  // The partial score arrays and the staging rows of the compaction share their memory: the
+  // selection has read the last partial before the merge kernel (launched after it, on the same
+  // stream) writes the first staged row, and the next block's scoring pass writes partials only
+  // after the move kernel has read the last one (the scratch set is the layer's until then).
+  const size_t partial_bytes = align_up(H * L.max_partials * L.cand_stride * 4);
+  const size_t stage_bytes = align_up(H * B * D * 2);
+  L.partial_off = s;
+  L.stage_k_off = s;
+  L.stage_v_off = s + stage_bytes;
+  s += partial_bytes > 2 * stage_bytes ? partial_bytes : 2 * stage_bytes;
   L.scores_off = s; s = align_up(s + H * L.cand_stride * 4);
   L.keep_off = s; s = align_up(s + H * L.cand_stride);
   L.dst_off = s; s = align_up(s + H * L.cand_stride * 4);
   L.counts_off = s; s = align_up(s + H * sizeof(HeadCounts));
   L.moves_off = s; s = align_up(s + H * B * sizeof(MoveEntry));
   L.dsts_off = s; s = align_up(s + H * B * sizeof(DstEntry));
-  L.stage_k_off = s; s = align_up(s + H * B * D * 2);
-  L.stage_v_off = s; s = align_up(s + H * B * D * 2);
   L.stage_w_off = s; s = align_up(s + H * B * 4);
   L.set_bytes = s;
   L.set_off = off;
