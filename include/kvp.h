@@ -283,6 +283,17 @@ int kvp_set_attention_shape(kvp_cache* cache, int32_t shape);
  * than 64 workgroups per KV head always use the separate kernel. */
 int kvp_set_score_sweep(kvp_cache* cache, int32_t fused);
 
+/* Scoring passes of kvp_prefill_chunk_proxy and kvp_prefill_chunk_keydiff put off
+ * until the compaction.  0 (the default): each call launches its scoring pass
+ * itself.  1: the call launches the attention only and leaves the layer PENDING
+ * with its scores still to come; kvp_compact or kvp_compact_layers launches them
+ * first -- kvp_compact_layers for up to 16 layers of the range per launch, which
+ * is what makes it worth while: these passes are launch-sized for one layer.
+ * The result is the same bit for bit.  While a layer waits, its q_obs (and, as
+ * always, its k and v) must stay valid, and kvp_debug_last has nothing to show
+ * for it.  kvp_prefill_block does the same by itself and ignores this setting. */
+int kvp_set_deferred_scoring(kvp_cache* cache, int32_t on);
+
 /* Inspection of the last block of a layer (device pointers, valid until the
  * layer's scratch set is reused).  n_cand = c + n of that block; candidates are
  * cache slots 0..c-1 then block tokens.

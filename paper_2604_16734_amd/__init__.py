@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     kvp_strerror, kvp_cache_bytes, kvp_persistent_bytes, kvp_init_cache, kvp_prefill_chunk,
     kvp_prefill_chunk_proxy, kvp_prefill_chunk_keydiff, kvp_prefill_block, kvp_prefill_join,
     KVP_SCORE_OWN, KVP_SCORE_PROXY, KVP_SCORE_KEYDIFF,
-    kvp_compact, kvp_compact_layers, kvp_decode_step, kvp_decode_step_static, KVP_STATIC_SCRATCH_BYTES, KVP_STATIC_MIN_SPLITS,
+    kvp_compact, kvp_compact_layers, kvp_set_deferred_scoring, kvp_decode_step, kvp_decode_step_static, KVP_STATIC_SCRATCH_BYTES, KVP_STATIC_MIN_SPLITS,
     kvp_decode_ready, kvp_set_state, kvp_set_attention_shape, kvp_set_score_sweep, kvp_debug_last,
     kvp_profile_enable,
     kvp_profile_read, kvp_kernel_name, kvp_debug_totals, TOTALS, kvp_probe_mfma, kvp_probe_copy, kvp_free_cache,

@@ -93,6 +93,8 @@ def lib():
         L.kvp_prefill_join.argtypes = [vp, vp, vp]
         L.kvp_compact.restype = ctypes.c_int
         L.kvp_compact.argtypes = [vp, i32, vp, vp]
+        L.kvp_set_deferred_scoring.restype = ctypes.c_int
+        L.kvp_set_deferred_scoring.argtypes = [vp, i32]
         L.kvp_compact_layers.restype = ctypes.c_int
         L.kvp_compact_layers.argtypes = [vp, i32, i32, vp]
         L.kvp_decode_step.restype = ctypes.c_int
@@ -203,6 +205,10 @@ def kvp_prefill_join(handle, stream=0, side_stream=None):
 
 def kvp_compact(handle, layer, scores_override=None, stream=0):
     return lib().kvp_compact(handle, layer, scores_override, stream)
+
+
+def kvp_set_deferred_scoring(handle, on):
+    return lib().kvp_set_deferred_scoring(handle, on)
 
 
 def kvp_compact_layers(handle, first_layer, n_layers, stream=0):
@@ -439,6 +445,9 @@ class Cache:
 
     def set_attention_shape(self, shape):
         _check(kvp_set_attention_shape(self.handle, shape), "kvp_set_attention_shape")
+
+    def set_deferred_scoring(self, on):
+        _check(kvp_set_deferred_scoring(self.handle, on), "kvp_set_deferred_scoring")
 
     def set_score_sweep(self, fused):
         _check(kvp_set_score_sweep(self.handle, fused), "kvp_set_score_sweep")

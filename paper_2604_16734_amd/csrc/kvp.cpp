@@ -139,6 +139,7 @@ struct kvp_cache {
   bool dry;
   int attn_shape = -1;                // kvp_set_attention_shape; < 0: chosen per launch
   bool fused_scores = true;           // kvp_set_score_sweep: scores out of the attention launch itself
+  bool deferred_scoring = false;      // kvp_set_deferred_scoring: proxy and key-only scoring at the compaction
   float* static_scratch = nullptr;    // the file-scope scratch array on this cache's device
   size_t static_scratch_floats = 0;
   bool profiling = false;
@@ -277,9 +278,16 @@ int run_compact(kvp_cache* c, int first, int count, const float* scores_override
 
 // kvp_compact for layers [first, first + count): one group launch when they hold the same block,
 // one layer at a time otherwise.  Every layer must be PENDING.
+int score_deferred_layers(kvp_cache* c, int first, int count, hipStream_t s);
+
 int compact_layers(kvp_cache* c, int first, int count, const float* scores_override, hipStream_t s) {
   for (int i = 0; i < count; ++i)
-    if (c->layers[first + i].state != PENDING || c->layers[first + i].unscored != 0) return KVP_ESTATE;
+    if (c->layers[first + i].state != PENDING) return KVP_ESTATE;
+  {
+    // scoring passes that were put off (kvp_set_deferred_scoring) come first, grouped like the rest
+    const int rc = score_deferred_layers(c, first, count, s);
+    if (rc) return rc;
+  }
   bool same = count <= kMaxGroupLayers && (scores_override == nullptr || count == 1);
   const Layer& A = c->layers[first];
   for (int i = 1; i < count && same; ++i) {
@@ -634,12 +642,14 @@ int kvp_prefill_chunk(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t 
 int kvp_prefill_chunk_proxy(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
                             const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs,
                             void* stream) {
-  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, kScoreProxy, stream);
+  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, q_obs, n_obs, kScoreProxy, stream,
+                      c && c->deferred_scoring);
 }
 
 int kvp_prefill_chunk_keydiff(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
                               const void* k, const void* v, void* out, void* stream) {
-  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, nullptr, 0, kScoreKeydiff, stream);
+  return prefill_impl(c, layer, token_begin, n_tokens, q, k, v, out, nullptr, 0, kScoreKeydiff, stream,
+                      c && c->deferred_scoring);
 }
 
 int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void* stream) {
@@ -838,6 +848,12 @@ int kvp_set_state(kvp_cache* c, int32_t layer, int32_t count, int32_t next_token
 int kvp_set_attention_shape(kvp_cache* c, int32_t shape) {
   if (!c || shape < -1 || shape > 2) return KVP_EINVAL;
   c->attn_shape = shape;
+  return KVP_OK;
+}
+
+int kvp_set_deferred_scoring(kvp_cache* c, int32_t on) {
+  if (!c || (on != 0 && on != 1)) return KVP_EINVAL;
+  c->deferred_scoring = on != 0;
   return KVP_OK;
 }
 

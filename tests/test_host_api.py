@@ -276,6 +276,26 @@ def test_compact_layers_state_machine():
             rc, vw = K.kvp_decode_ready(h, layer)
             assert rc == K.KVP_OK and vw.next_token == (32 if layer < nl - 1 else 24)
         assert K.kvp_compact_layers(h, 2, 3) == K.KVP_ESTATE
+        # scoring passes put off until the compaction: the per-layer calls and both ways of compacting
+        assert K.kvp_set_deferred_scoring(None, 1) == K.KVP_EINVAL
+        assert K.kvp_set_deferred_scoring(h, 2) == K.KVP_EINVAL
+        assert K.kvp_set_deferred_scoring(h, 1) == K.KVP_OK
+        t = 32                                     # every layer but the last stands at token 32
+        assert K.kvp_prefill_chunk(h, nl - 1, 24, 8, 0, 0, 0, 0) == K.KVP_OK
+        assert K.kvp_compact(h, nl - 1) == K.KVP_OK
+        while t < wl.budget + 2 * wl.chunk:        # well into the blocks that evict
+            for layer in range(nl):
+                if layer % 2:
+                    assert K.kvp_prefill_chunk_keydiff(h, layer, t, wl.chunk, 0, 0, 0, 0) == K.KVP_OK
+                else:
+                    assert K.kvp_prefill_chunk_proxy(h, layer, t, wl.chunk, 0, 0, 0, 0, 0, 8) == K.KVP_OK
+            assert K.kvp_compact(h, 0) == K.KVP_OK
+            assert K.kvp_compact_layers(h, 1, nl - 1) == K.KVP_OK
+            t += wl.chunk
+            for layer in range(nl):
+                rc, vw = K.kvp_decode_ready(h, layer)
+                assert rc == K.KVP_OK and (vw.count, vw.next_token) == (min(wl.budget, t), t)
+        assert K.kvp_set_deferred_scoring(h, 0) == K.KVP_OK
     finally:
         K.kvp_free_cache(h)
 
