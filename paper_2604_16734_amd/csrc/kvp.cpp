@@ -278,16 +278,10 @@ int run_compact(kvp_cache* c, int first, int count, const float* scores_override
 
 // kvp_compact for layers [first, first + count): one group launch when they hold the same block,
 // one layer at a time otherwise.  Every layer must be PENDING.
-int score_deferred_layers(kvp_cache* c, int first, int count, hipStream_t s);
-
 int compact_layers(kvp_cache* c, int first, int count, const float* scores_override, hipStream_t s) {
+  // (a scoring pass that was put off is the caller's to launch first: score_deferred_layers)
   for (int i = 0; i < count; ++i)
-    if (c->layers[first + i].state != PENDING) return KVP_ESTATE;
-  {
-    // scoring passes that were put off (kvp_set_deferred_scoring) come first, grouped like the rest
-    const int rc = score_deferred_layers(c, first, count, s);
-    if (rc) return rc;
-  }
+    if (c->layers[first + i].state != PENDING || c->layers[first + i].unscored != 0) return KVP_ESTATE;
   bool same = count <= kMaxGroupLayers && (scores_override == nullptr || count == 1);
   const Layer& A = c->layers[first];
   for (int i = 1; i < count && same; ++i) {
@@ -413,7 +407,7 @@ namespace {
 // A short list of proxy queries would leave the attention kernel with a handful of workgroups that
 // each walk all keys: rowstat_kernel spreads the keys instead.  Its per-block partials borrow the
 // memory of the column-sum partials, which the scoring pass only writes afterwards.
-bool proxy_by_rowstat(const kvp_cache* c, int n_cand, int n_obs) {
+static bool proxy_by_rowstat(const kvp_cache* c, int n_cand, int n_obs) {
   const kvp_config& cfg = c->cfg;
   const Layout& lay = c->lay;
   const int n_kb = rowstat_key_blocks(n_cand);
@@ -424,7 +418,7 @@ bool proxy_by_rowstat(const kvp_cache* c, int n_cand, int n_obs) {
 
 // The scoring kernels' arguments for `layer` (the first layer of a group, or the only one) with
 // `count` entries in its cache and a block of `n_tokens`; the group and the queries are the caller's.
-RowstatArgs rowstat_args(kvp_cache* c, int layer, int count, int n_tokens, int n_obs) {
+static RowstatArgs rowstat_args(kvp_cache* c, int layer, int count, int n_tokens, int n_obs) {
   const kvp_config& cfg = c->cfg;
   const Layout& lay = c->lay;
   unsigned char* set = c->set(layer);
@@ -440,7 +434,7 @@ RowstatArgs rowstat_args(kvp_cache* c, int layer, int count, int n_tokens, int n
   return ra;
 }
 
-ColsumArgs colsum_args(kvp_cache* c, int layer, int count, int n_tokens, int n_rows, int shift) {
+static ColsumArgs colsum_args(kvp_cache* c, int layer, int count, int n_tokens, int n_rows, int shift) {
   const kvp_config& cfg = c->cfg;
   const Layout& lay = c->lay;
   unsigned char* set = c->set(layer);
@@ -457,7 +451,7 @@ ColsumArgs colsum_args(kvp_cache* c, int layer, int count, int n_tokens, int n_r
   return cs;
 }
 
-KeydiffArgs keydiff_args(kvp_cache* c, int layer, int count, int n_tokens) {
+static KeydiffArgs keydiff_args(kvp_cache* c, int layer, int count, int n_tokens) {
   const kvp_config& cfg = c->cfg;
   const Layout& lay = c->lay;
   KeydiffArgs ka{};
@@ -472,7 +466,7 @@ KeydiffArgs keydiff_args(kvp_cache* c, int layer, int count, int n_tokens) {
 // The scoring pass (proxy queries: row statistics, then column sums; or the keys alone) for `count`
 // consecutive layers whose blocks went through prefill_impl with `defer`: one launch of each
 // kernel for up to kMaxGroupLayers layers in the same state, else layer by layer.
-int score_deferred_layers(kvp_cache* c, int first, int count, hipStream_t s) {
+static int score_deferred_layers(kvp_cache* c, int first, int count, hipStream_t s) {
   const kvp_config& cfg = c->cfg;
   for (int done = 0; done < count;) {
     Layer& A = c->layers[first + done];
@@ -521,7 +515,7 @@ int score_deferred_layers(kvp_cache* c, int first, int count, hipStream_t s) {
 // `defer`: leave the scoring pass of proxy queries or of the keys alone to score_deferred_layers,
 // which launches it for a group of layers at once (kvp_prefill_block); the layer is PENDING and
 // `unscored` until then.
-int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
+static int prefill_impl(kvp_cache* c, int32_t layer, int32_t token_begin, int32_t n_tokens, const void* q,
                  const void* k, const void* v, void* out, const void* q_obs, int32_t n_obs, int mode,
                  void* stream, bool defer = false) {
   const bool proxy = mode == kScoreProxy;
@@ -654,6 +648,10 @@ int kvp_prefill_chunk_keydiff(kvp_cache* c, int32_t layer, int32_t token_begin, 
 
 int kvp_compact(kvp_cache* c, int32_t layer, const float* scores_override, void* stream) {
   if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVP_EINVAL;
+  if (c->layers[layer].state != PENDING) return KVP_ESTATE;
+  // a scoring pass that was put off (kvp_set_deferred_scoring) comes first
+  const int rc = score_deferred_layers(c, layer, 1, static_cast<hipStream_t>(stream));
+  if (rc) return rc;
   return compact_layers(c, layer, 1, scores_override, static_cast<hipStream_t>(stream));
 }
 
@@ -662,6 +660,11 @@ int kvp_compact_layers(kvp_cache* c, int32_t first_layer, int32_t n_layers, void
     return KVP_EINVAL;
   for (int i = 0; i < n_layers; ++i)
     if (c->layers[first_layer + i].state != PENDING) return KVP_ESTATE;
+  {
+    // scoring passes that were put off (kvp_set_deferred_scoring) come first, grouped like the rest
+    const int rc = score_deferred_layers(c, first_layer, n_layers, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+  }
   for (int done = 0; done < n_layers; done += kMaxGroupLayers) {
     const int count = n_layers - done < kMaxGroupLayers ? n_layers - done : kMaxGroupLayers;
     const int rc = compact_layers(c, first_layer + done, count, nullptr, static_cast<hipStream_t>(stream));
