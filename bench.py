@@ -182,6 +182,32 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         torch.cuda.synchronize()
         t_kd = (time.perf_counter() - t_kd) / steps
         keydiff = {"tokens_per_s": round(wl.n_tokens / t_kd, 1), "ms_per_step": round(1e3 * t_kd, 4)}
+    layerwise = None
+    if variants:
+        # the order of calls a model has: one attention call per layer as the block moves up the
+        # stack, one kvp_compact_layers per block (runtime.LayerwisePrefill)
+        lcache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
+                         wl.segments, merge=True, scratch_sets=wl.n_layers, device=device)
+        ldriver = K.LayerwisePrefill(lcache, wl.n_layers)
+
+        def layerwise_steps(count):
+            for _ in range(count):
+                for layer in range(wl.n_layers):
+                    lcache.set_state(layer, 0, 0)
+                for t0, n in ranges:
+                    for layer in range(wl.n_layers):
+                        q, k, v = (x[t0:t0 + n] for x in data[layer])
+                        ldriver.layer(layer, t0, q, k, v, out=outs[layer][:n])
+                    ldriver.end_block()
+        layerwise_steps(1)
+        torch.cuda.synchronize()
+        t_lw = time.perf_counter()
+        layerwise_steps(steps)
+        torch.cuda.synchronize()
+        t_lw = (time.perf_counter() - t_lw) / steps
+        layerwise = {"tokens_per_s": round(wl.n_tokens / t_lw, 1), "ms_per_step": round(1e3 * t_lw, 4),
+                     "scratch_sets": wl.n_layers}
+        lcache.close()
     bulk = None
     if variants and wl.budget > wl.chunk and wl.budget + wl.budget <= 8192 and wl.n_tokens > wl.budget:
         # hybrid execution (Sec. 4.3): the first `budget` tokens in one causal pass, then blocks
@@ -239,6 +265,7 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
     res = {
         "decode_step": decode,
         "bulk_first_pass": bulk,
+        "layerwise_order": layerwise,
         "keydiff_scoring": keydiff,
         "proxy_scoring": proxy,
         "tokens_per_s": wl.n_tokens / (elapsed / steps),
@@ -539,6 +566,7 @@ def main():
         "proxy_query_scoring": main_res["proxy_scoring"],
         "keydiff_scoring": main_res["keydiff_scoring"],
         "bulk_first_pass": main_res["bulk_first_pass"],
+        "layerwise_order": main_res["layerwise_order"],
         "decode_step": main_res["decode_step"],
     }
     if not args.no_cpu:

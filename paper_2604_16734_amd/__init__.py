@@ -16,4 +16,4 @@ from .binding import (  # noqa: F401
     kvp_profile_read, kvp_kernel_name, kvp_debug_totals, TOTALS, kvp_probe_mfma, kvp_probe_copy, kvp_free_cache,
     Cache,
 )
-from .runtime import Prefill  # noqa: F401
+from .runtime import Prefill, LayerwisePrefill  # noqa: F401

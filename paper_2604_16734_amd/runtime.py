@@ -11,6 +11,14 @@ between the two streams live in the library (kvp_prefill_block): one call per
 block, so that the host keeps ahead of the GPU.
 
 Both streams have the default priority.
+
+`Prefill` needs every layer's Q, K, V of a block at once, which a benchmark on
+synthetic layers has and a model does not: there, layer l + 1 only exists once
+layer l is through.  `LayerwisePrefill` is the order of calls for that case:
+one attention call per layer as the block moves up the stack, and one
+kvp_compact_layers for the stack when the block is through, which compacts (and,
+for proxy or key-only scoring, scores) the layers in groups of up to 16 per
+kernel launch.
 """
 from __future__ import annotations
 
@@ -76,3 +84,41 @@ class Prefill:
         """Make the current stream wait for the compactions still in flight."""
         main, side = self._streams()
         B._check(B.kvp_prefill_join(self.cache.handle, main, side), "kvp_prefill_join")
+
+
+class LayerwisePrefill:
+    """One block at a time, one layer at a time: `layer(...)` for layers 0, 1, ... as the model
+    produces their Q, K, V, then `end_block()`.  The cache must have been created with
+    scratch_sets >= n_layers (every layer stays pending until the block is through)."""
+
+    def __init__(self, cache, n_layers):
+        if (int(cache.cfg.scratch_sets) or 1) < n_layers:
+            raise ValueError("a scratch set per layer is needed: create the cache with scratch_sets >= n_layers")
+        self.cache = cache
+        self.n_layers = n_layers
+        self._held = []          # K, V and proxy queries of the block: read again by end_block()
+        self._next = 0
+        cache.set_deferred_scoring(1)
+
+    def layer(self, layer, t0, q, k, v, out=None, q_obs=None, keydiff=False):
+        """Attention of the block for `layer` (Eq. 1); the scores come from the block's own queries
+        in the same launch, or later (end_block) from `q_obs` or from the keys alone."""
+        if layer != self._next:
+            raise ValueError("layers go in order: expected layer %d" % self._next)
+        if keydiff:
+            out = self.cache.prefill_chunk_keydiff(layer, t0, q, k, v, out=out)
+        elif q_obs is not None:
+            out = self.cache.prefill_chunk_proxy(layer, t0, q, k, v, q_obs, out=out)
+        else:
+            out = self.cache.prefill_chunk(layer, t0, q, k, v, out=out)
+        self._held.append((k, v, q_obs))
+        self._next += 1
+        return out
+
+    def end_block(self):
+        """Scores still to come, then select, merge and move, for all layers of the block."""
+        if self._next != self.n_layers:
+            raise ValueError("the block has only been through %d of %d layers" % (self._next, self.n_layers))
+        self.cache.compact_layers(0, self.n_layers)
+        self._held.clear()       # enqueued on the same stream: the allocator may hand the memory out again
+        self._next = 0

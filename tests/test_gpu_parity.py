@@ -644,6 +644,54 @@ def test_compact_layers_is_the_per_layer_compaction(name, layers, scoring):
                                y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
 
 
+@pytest.mark.parametrize("scoring", ["own", "proxy", "keydiff"])
+def test_layerwise_driver_matches_the_block_driver(scoring):
+    """The two orders of calls of runtime.py, a whole block at once (Prefill) and layer by layer with
+    one kvp_compact_layers per block (LayerwisePrefill, freshly allocated K and V per layer as a
+    model would have them), leave the same caches and outputs bit for bit."""
+    wl = get_workload("tiled_image")
+    layers = wl.n_layers
+    data = [tuple(U.bits_to_torch(x) for x in layer_inputs(wl, l)) for l in range(layers)]
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    obs = [torch.randn((24, wl.n_q_heads, wl.head_dim), generator=gen, device=DEV).to(torch.bfloat16)
+           for _ in range(layers)]
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)
+    results = []
+    for layerwise in (False, True):
+        cache = K.Cache(layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments,
+                        merge=True, scratch_sets=layers, device=DEV)
+        outs = [torch.zeros((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=DEV)
+                for _ in range(layers)]
+        if layerwise:
+            driver = K.LayerwisePrefill(cache, layers)
+            for t0, n in ranges:
+                for l in range(layers):
+                    q, k, v = (x[t0:t0 + n].clone() for x in data[l])
+                    driver.layer(l, t0, q, k, v, out=outs[l][:n], q_obs=obs[l] if scoring == "proxy" else None,
+                                 keydiff=scoring == "keydiff")
+                    del q, k, v
+                driver.end_block()
+        else:
+            driver = K.Prefill(cache, layers)
+            for t0, n in ranges:
+                driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n],
+                             (lambda l: obs[l]) if scoring == "proxy" else None, scoring == "keydiff")
+            driver.finish()
+        torch.cuda.synchronize()
+        state = []
+        for l in range(layers):
+            k, v, idx, w, count, nxt = cache.decode_ready(l)
+            state.append((k[:, :count].clone(), v[:, :count].clone(), idx[:, :count].clone(), w[:, :count].clone(),
+                          count, nxt, outs[l].clone()))
+        results.append(state)
+        cache.close()
+    for a, b in zip(*results):
+        assert a[4] == b[4] and a[5] == b[5]
+        for x, y in zip(a[:4] + (a[6],), b[:4] + (b[6],)):
+            assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                               y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
+
+
 def test_real_cache_refuses_null_tensors():
     """A cache on a live allocation (not a dry run) returns KVP_EINVAL for a null tensor before it
     enqueues anything, and stays usable."""
