@@ -137,7 +137,8 @@ def attainable_peaks(device):
                    "kvp_probe_copy: 256 MiB, read + written bytes, best of four grid sizes; medians of 5" % cus}
 
 
-def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=16, variants=True):
+def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, n_obs=0, scratch_sets=16, variants=True,
+                   eq1_alone=True, score_sweep=1):
     import torch
     import paper_2604_16734_amd as K
     from kvp_workload import chunk_ranges
@@ -148,6 +149,7 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
     scratch_sets = max(2 if two else 1, min(scratch_sets, wl.n_layers))
     cache = K.Cache(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk,
                     wl.segments, merge=True, scratch_sets=scratch_sets, device=device)
+    cache.set_score_sweep(score_sweep)
     driver = K.Prefill(cache, wl.n_layers, overlap=two)
     outs = [torch.empty((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=device)
             for _ in range(wl.n_layers)]
@@ -306,21 +308,23 @@ def bench_workload(wl, steps, warmup, device, threads, profile=True, streams=1, 
         done = {k: v - totals_before[k] for k, v in cache.totals().items()}
         # ---- the same pass with the scores taken by the separate kernel: the attention launch then
         # holds Eq. 1 alone (what earlier versions of this line reported as the attention roofline)
-        cache.set_score_sweep(0)
-        cache.profile_enable(True)
-        run_steps(K.Prefill(cache, wl.n_layers, overlap=False), cache, wl, data, ranges, prof_steps, outs)
-        torch.cuda.synchronize()
-        alone = cache.profile_read()
-        cache.profile_enable(False)
-        cache.set_score_sweep(1)
-        a_n, a_ms, _ = alone["attention"]
-        c_n, c_ms, _ = alone["colsum"]
-        res["eq1_alone"] = {
-            "avg_launch_us": round(1e3 * a_ms / a_n, 2),
-            "achieved": round(flops_step * prof_steps / (a_ms * 1e-3) / 1e12, 2),
-            "separate_scoring_avg_launch_us": round(1e3 * c_ms / c_n, 2) if c_n else None,
-            "with_separate_scoring_tflops": round(flops_step * prof_steps / ((a_ms + c_ms) * 1e-3) / 1e12, 2),
-        }
+        res["eq1_alone"] = None
+        if eq1_alone:
+            cache.set_score_sweep(0)
+            cache.profile_enable(True)
+            run_steps(K.Prefill(cache, wl.n_layers, overlap=False), cache, wl, data, ranges, prof_steps, outs)
+            torch.cuda.synchronize()
+            alone = cache.profile_read()
+            cache.profile_enable(False)
+            cache.set_score_sweep(score_sweep)
+            a_n, a_ms, _ = alone["attention"]
+            c_n, c_ms, _ = alone["colsum"]
+            res["eq1_alone"] = {
+                "avg_launch_us": round(1e3 * a_ms / a_n, 2),
+                "achieved": round(flops_step * prof_steps / (a_ms * 1e-3) / 1e12, 2),
+                "separate_scoring_avg_launch_us": round(1e3 * c_ms / c_n, 2) if c_n else None,
+                "with_separate_scoring_tflops": round(flops_step * prof_steps / ((a_ms + c_ms) * 1e-3) / 1e12, 2),
+            }
         row = wl.head_dim * 2                       # bytes of one K or V row
         appended, select_bytes, colsum_flops, evicting_launches = 0, 0, 0, 0
         c = 0
@@ -415,6 +419,12 @@ def main():
                     help="also time proxy-query and key-only scoring, the bulk first pass and the decode step")
     ap.add_argument("--peaks", type=int, default=1,
                     help="also measure what this GPU attains on a register-resident bf16 MFMA loop and a device copy")
+    ap.add_argument("--score-sweep", type=int, default=1, choices=(0, 1),
+                    help="1: the scores of Eq. 4 out of the attention launch's second sweep (the library's default); "
+                         "0: by the separate column-sum kernel (for profiles of the attention launch with Eq. 1 alone)")
+    ap.add_argument("--eq1-alone", type=int, default=1,
+                    help="also time one pass with the scores taken by the separate kernel (the attention launch "
+                         "then holds Eq. 1 alone); 0 keeps that pass out of a counter run")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -439,14 +449,15 @@ def main():
         torch.cuda.synchronize()
         del a, b
     main_res = bench_workload(wl, args.steps, args.warmup, device, threads, streams=args.streams, n_obs=args.n_obs,
-                              scratch_sets=args.scratch_sets, variants=bool(args.variants))
+                              scratch_sets=args.scratch_sets, variants=bool(args.variants), eq1_alone=bool(args.eq1_alone),
+                              score_sweep=args.score_sweep)
 
     others = {}
     if args.others:
         for w in WORKLOADS:
             if w.name != wl.name:
                 r = bench_workload(w, max(3, args.steps // 2), 2, device, threads, profile=True, streams=args.streams,
-                                   scratch_sets=args.scratch_sets, variants=False)
+                                   scratch_sets=args.scratch_sets, variants=False, eq1_alone=False)
                 others[w.name] = {
                     "tokens_per_s": round(r["tokens_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4),
                     "attention_tflops": round(r["attention_tflops"], 2),
@@ -543,7 +554,8 @@ def main():
                     "with Eq. 1 only, and what the two launches reach together",
             "eq1_alone": dict(main_res["eq1_alone"], unit="TFLOP/s",
                               frac=round(main_res["eq1_alone"]["achieved"] / PEAK_BF16_TFLOPS, 4),
-                              with_separate_scoring_frac=round(main_res["eq1_alone"]["with_separate_scoring_tflops"] / PEAK_BF16_TFLOPS, 4)),
+                              with_separate_scoring_frac=round(main_res["eq1_alone"]["with_separate_scoring_tflops"] / PEAK_BF16_TFLOPS, 4))
+                         if main_res["eq1_alone"] else None,
         },
         "rooflines": rooflines,
         "select_merge_move": {
