@@ -645,6 +645,40 @@ def test_compact_layers_is_the_per_layer_compaction(name, layers, scoring):
                                y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
 
 
+def test_bench_launch_configuration_changes_nothing():
+    """bench.py's default order at its own shape: everything in line on one stream, sixteen scratch
+    sets, so that select, merge and move go out once per sixteen layers of long_video.  The first
+    five blocks (two that only append, three that evict) of sixteen layers must leave the caches
+    and outputs of the layer-by-layer order with one scratch set, bit for bit."""
+    wl = get_workload("long_video")
+    layers = 16
+    data = [tuple(U.bits_to_torch(x) for x in layer_inputs(wl, l)) for l in range(layers)]
+    ranges = chunk_ranges(wl.n_tokens, wl.chunk)[:5]
+    results = []
+    for sets in (1, 16):
+        cache = K.Cache(layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.chunk, wl.segments,
+                        merge=True, scratch_sets=sets, device=DEV)
+        driver = K.Prefill(cache, layers, overlap=False)
+        outs = [torch.zeros((wl.chunk, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=DEV)
+                for _ in range(layers)]
+        for t0, n in ranges:
+            driver.block(t0, lambda l: tuple(x[t0:t0 + n] for x in data[l]), lambda l: outs[l][:n])
+        driver.finish()
+        torch.cuda.synchronize()
+        state = []
+        for l in range(layers):
+            k, v, idx, w, count, nxt = cache.decode_ready(l)
+            state.append((k[:, :count].clone(), v[:, :count].clone(), idx[:, :count].clone(), w[:, :count].clone(),
+                          count, nxt, outs[l].clone()))
+        results.append(state)
+        cache.close()
+    for a, b in zip(*results):
+        assert a[4] == b[4] and a[5] == b[5]
+        for x, y in zip(a[:4] + (a[6],), b[:4] + (b[6],)):
+            assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                               y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
+
+
 @pytest.mark.parametrize("scoring", ["own", "proxy", "keydiff"])
 def test_layerwise_driver_matches_the_block_driver(scoring):
     """The two orders of calls of runtime.py, a whole block at once (Prefill) and layer by layer with
