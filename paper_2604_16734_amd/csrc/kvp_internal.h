@@ -26,6 +26,7 @@ constexpr int kDecodeTile = 64;                 // keys per workgroup step of th
 constexpr int kDecodeMaxSplits = 128;
 constexpr int kDecodeGroupLimit = 16;           // query heads per KV head the decode kernel is built for
 constexpr int kCompactThreads = 256;
+constexpr int kCompactTargetWorkgroups = 4096;  // a merge or move launch is capped at about this many workgroups
 
 // bytes of the select kernel's region that is first the radix histogram and then the compaction lists
 constexpr size_t select_region_bytes(size_t cand_pad) {
