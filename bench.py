@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, vendor figure
 # HBM bytes per attention launch (fetch + write) at the long_video steady state, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (launch-weighted mean,
 # counters scaled by what they read for a plain 256 MiB copy); None for a workload not measured
-ATTENTION_TRAFFIC_BYTES = {"long_video": 52237892}
+ATTENTION_TRAFFIC_BYTES = {"long_video": 52326293}
 
 
 def attention_flops(wl, t0_n_pairs):
